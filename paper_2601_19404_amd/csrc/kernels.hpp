@@ -1,0 +1,141 @@
+// Launchers of the HIP kernels behind the RPO rollout C ABI (host-callable).
+// Every launcher validates nothing: callers (rpo_api.hip) check shapes first.
+#pragma once
+
+#include "common.hpp"
+
+namespace rpo {
+
+enum DType : int { kF32 = 0, kBF16 = 1 };
+
+inline size_t dtype_size(int dt) { return dt == kF32 ? 4 : 2; }
+
+// One packed sequence of token rows inside a chunk pushed through the layers.
+struct SeqDesc {
+    int row_start;  // first row of the sequence in the packed row buffer
+    int n_rows;     // rows of this sequence in the buffer
+    int pos0;       // absolute position (0-based over prompt || answer) of its first row
+    int table_off;  // offset (in int32) of its page table inside the table array
+};
+
+// ---- GEMM: C[M,N] (op)= A[M,K] * W[N,K]^T, fp32 accumulation -----------------
+enum Epilogue : int {
+    kEpiStore = 0,     // C has the input dtype
+    kEpiStoreF32 = 1,  // C is fp32
+    kEpiAddF32 = 2,    // C is fp32 and is accumulated into (residual stream)
+};
+struct GemmArgs {
+    const void* A;
+    int64_t lda;
+    const void* W;
+    int64_t ldw;
+    void* C;
+    int64_t ldc;
+    int M, N, K;
+    int dtype;     // element type of A and W
+    int epilogue;  // Epilogue
+    int path;      // 0 = pick, 1 = force the generic (non-MFMA) kernel
+};
+hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
+
+// ---- elementwise ---------------------------------------------------------------
+// x[r, :] = embed[tokens[idx(r)], :] as fp32, idx(r) = tok_index ? tok_index[r] : r;
+// out-of-range ids give a zero row.
+hipError_t launch_embed(const int32_t* tokens, const int32_t* tok_index, const void* embed, int dtype,
+                        int vocab, int d, float* x, int rows, hipStream_t s);
+// h[r, :] = x[src(r), :] / sqrt(mean(x^2) + eps) * gain, src(r) = row_idx ? row_idx[r] : r.
+// x fp32, gain and h in `dtype`.
+hipError_t launch_rmsnorm(const float* x, const int32_t* row_idx, const void* gain, int dtype, int d,
+                          float eps, void* h, int rows, hipStream_t s);
+// act[r, j] = silu(gu[r, j]) * gu[r, F + j]
+hipError_t launch_swiglu(const void* gu, int dtype, int F, void* act, int rows, hipStream_t s);
+// dst[r, :] = src[row_idx[r], :] (fp32 rows of width d)
+hipError_t launch_gather_rows(const float* src, const int32_t* row_idx, int d, float* dst, int rows,
+                              hipStream_t s);
+
+// Rotate q and k of every row by its position, write k and v into the row's KV page.
+struct RopeKvArgs {
+    void* qkv;  // [rows, (Hq + 2 Hkv) dh], q rotated in place
+    int dtype;
+    int rows;
+    int Hq, Hkv, dh;
+    const float* rope;      // [max_pos, dh/2, 2] (cos, sin)
+    const int32_t* row_seq;  // row -> sequence index, or NULL: sequence = row
+    const SeqDesc* seqs;
+    int pos_add;             // added to every position (decode step)
+    const int32_t* tables;
+    const uint8_t* active;  // per row, or NULL
+    void* kv_pool;
+    KvGeom geom;
+    int layer;
+};
+hipError_t launch_rope_kv(const RopeKvArgs& a, hipStream_t s);
+
+// Copy the partially filled last prefix page of each group into the first private
+// page of each of its rollouts, all layers.  src_page/dst_page per rollout; src < 0 = nothing.
+hipError_t launch_fork_copy(void* kv_pool, int dtype, KvGeom geom, int n_layers, const int32_t* src_page,
+                            const int32_t* dst_page, int n_rollouts, hipStream_t s);
+
+// ---- attention over the paged cache --------------------------------------------
+// Causal attention of packed rows: row i of sequence s (position pos0 + i + pos_add) sees
+// positions [0, pos0 + i + pos_add] of that sequence's pages.
+struct AttnArgs {
+    const void* q;  // [rows, q_stride]; head h at column h * dh
+    int64_t q_stride;
+    void* out;  // [rows, Hq * dh]
+    int dtype;
+    int rows;
+    int Hq, Hkv, dh;
+    const int32_t* row_seq;  // or NULL: sequence = row
+    const SeqDesc* seqs;
+    int n_seqs;
+    int max_seq_rows;  // largest n_rows among seqs (grid sizing)
+    int pos_add;
+    const int32_t* tables;
+    const uint8_t* active;  // per row, or NULL
+    const void* kv_pool;
+    KvGeom geom;
+    int layer;
+    float scale;
+    int path;  // 0 = pick, 1 = force generic
+};
+hipError_t launch_attn_chunk(const AttnArgs& a, hipStream_t s);
+
+// Decode attention with a shared prefix: rollout rows r = g * G + i, one new query row
+// each; rows of a group share the group's first shared_pages[g] pages.
+struct DecodeAttnArgs {
+    AttnArgs base;               // seqs = per-rollout descriptors (n_rows = 1)
+    int G;
+    const int32_t* shared_pages;  // per group: full prefix pages shared by its rollouts
+    int max_shared_pages;
+    int max_own_pages;  // private pages any rollout can hold at this step
+    float* partial;     // split-KV scratch
+    size_t partial_floats;
+};
+hipError_t launch_attn_decode(const DecodeAttnArgs& a, hipStream_t s);
+size_t attn_decode_partial_floats(int rows, int Hq, int dh, int max_shared_pages);
+
+// ---- sampling, log-probs, advantages -------------------------------------------
+struct SampleArgs {
+    const float* logits;
+    int n_logit_rows, vocab;
+    int64_t row_stride;
+    const int32_t* row_map;
+    int n_out_rows;
+    float inv_t;
+    uint64_t seed;
+    const uint64_t* seq_id;
+    uint32_t step;
+    int32_t* tokens_out;
+    float* logprob_out;
+};
+hipError_t launch_sample(const SampleArgs& a, hipStream_t s);
+
+// out[r] = logits[r, target[r]] * inv_t - logsumexp(logits[r, :] * inv_t)
+hipError_t launch_lse_gather(const float* logits, int64_t row_stride, int vocab, const int32_t* target,
+                             float inv_t, float* out, int rows, hipStream_t s);
+
+hipError_t launch_advantages(const float* rewards, int n_groups, int G, int ddof, float eps, float* adv,
+                             hipStream_t s);
+
+}  // namespace rpo

@@ -1,0 +1,247 @@
+// Temperature sampling, log-sum-exp gather and group-relative advantages.
+//
+// This translation unit is compiled with -ffp-contract=off: the sampler's
+// arithmetic is a bit-exact contract (see rpo_sample in rpo.h), every fp32
+// multiply and add below must round on its own.
+#include "kernels.hpp"
+
+namespace rpo {
+
+// ---------------------------------------------------------------------------
+// Philox4x32-10 (Salmon et al., SC'11): 10 rounds, multipliers 0xD2511F53 /
+// 0xCD9E8D57, Weyl key increments 0x9E3779B9 / 0xBB67AE85.
+// ---------------------------------------------------------------------------
+__device__ inline uint64_t philox_u64(uint64_t seed, uint64_t seq, uint32_t step) {
+    uint32_t c0 = step, c1 = (uint32_t)seq, c2 = (uint32_t)(seq >> 32), c3 = 0u;
+    uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        if (r) {
+            k0 += 0x9E3779B9u;
+            k1 += 0xBB67AE85u;
+        }
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n1 = (uint32_t)p1;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        const uint32_t n3 = (uint32_t)p0;
+        c0 = n0;
+        c1 = n1;
+        c2 = n2;
+        c3 = n3;
+    }
+    return ((uint64_t)c1 << 32) | c0;
+}
+
+// q = floor(2^x * 2^40) through the fixed polynomial; x = ((z - zmax) * inv_t) * log2(e).
+__device__ inline uint64_t weight_u64(float z, float zmax, float inv_t) {
+    float x = __fsub_rn(z, zmax);
+    x = __fmul_rn(x, inv_t);
+    x = __fmul_rn(x, 0x1.715476p+0f);
+    if (!(x >= -41.0f)) return 0ull;  // also catches NaN
+    const float n = __builtin_rintf(x);
+    const float f = __fsub_rn(x, n);
+    float p = 0x1.ffcbfcp-17f;
+    p = __fadd_rn(__fmul_rn(p, f), 0x1.430912p-13f);
+    p = __fadd_rn(__fmul_rn(p, f), 0x1.5d87fep-10f);
+    p = __fadd_rn(__fmul_rn(p, f), 0x1.3b2ab6p-7f);
+    p = __fadd_rn(__fmul_rn(p, f), 0x1.c6b08ep-5f);
+    p = __fadd_rn(__fmul_rn(p, f), 0x1.ebfbe0p-3f);
+    p = __fadd_rn(__fmul_rn(p, f), 0x1.62e430p-1f);
+    p = __fadd_rn(__fmul_rn(p, f), 1.0f);
+    // p in (0.7, 1.42), exponent e = n + 40 in [-1, 40]: p * 2^e < 2^41 is exact in fp64.
+    const double v = ldexp((double)p, (int)n + 40);
+    return (uint64_t)v;  // truncation toward zero == floor for v >= 0
+}
+
+__device__ inline uint64_t wave_sum_u64(uint64_t v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const uint32_t lo = __shfl_xor((uint32_t)v, o, kWave);
+        const uint32_t hi = __shfl_xor((uint32_t)(v >> 32), o, kWave);
+        v += ((uint64_t)hi << 32) | lo;
+    }
+    return v;
+}
+
+// One workgroup (4 waves) per output row.  The row is cut into segments of 256
+// logits (4 per lane); wave w owns segments w, w + 4, ...  Integer sums make the
+// result independent of this decomposition.
+constexpr int kSegLen = 256;
+constexpr int kMaxSeg = 1024;  // vocab <= 262144
+
+__global__ __launch_bounds__(256) void sample_kernel(SampleArgs a) {
+    __shared__ uint64_t seg_sum[kMaxSeg];
+    __shared__ float red[4];
+    __shared__ int pick_seg;
+    __shared__ uint64_t pick_rem;
+    const int r = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int src = a.row_map ? a.row_map[r] : r;
+    const float* z = a.logits + (int64_t)src * a.row_stride;
+    const int V = a.vocab;
+    const int n_seg = (V + kSegLen - 1) / kSegLen;
+
+    float zmax = -INFINITY;
+    for (int i = tid; i < V; i += 256) zmax = fmaxf(zmax, z[i]);
+    zmax = wave_max(zmax);
+    if (lane == 0) red[wave] = zmax;
+    __syncthreads();
+    zmax = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+
+    for (int sg = wave; sg < n_seg; sg += 4) {
+        const int i0 = sg * kSegLen + lane * 4;
+        uint64_t q = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (i0 + e < V) q += weight_u64(z[i0 + e], zmax, a.inv_t);
+        q = wave_sum_u64(q);
+        if (lane == 0) seg_sum[sg] = q;
+    }
+    __syncthreads();
+
+    if (wave == 0) {
+        // total, threshold, and the segment the threshold falls into
+        uint64_t loc = 0;
+        for (int sg = lane; sg < n_seg; sg += 64) loc += seg_sum[sg];
+        const uint64_t total = wave_sum_u64(loc);
+        const uint64_t u = philox_u64(a.seed, a.seq_id[r], a.step);
+        const uint64_t t = __umul64hi(u, total);
+        if (lane == 0) {
+            uint64_t run = 0;
+            int sg = 0;
+            for (; sg < n_seg - 1; ++sg) {
+                if (run + seg_sum[sg] > t) break;
+                run += seg_sum[sg];
+            }
+            pick_seg = sg;
+            pick_rem = t - run;  // < seg_sum[sg]
+        }
+    }
+    __syncthreads();
+    if (wave == 0) {
+        const int sg = pick_seg;
+        const uint64_t rem = pick_rem;
+        const int i0 = sg * kSegLen + lane * 4;
+        uint64_t q[4];
+        uint64_t mine = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            q[e] = (i0 + e < V) ? weight_u64(z[i0 + e], zmax, a.inv_t) : 0ull;
+            mine += q[e];
+        }
+        // exclusive prefix over lanes
+        uint64_t incl = mine;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const uint32_t lo = __shfl_up((uint32_t)incl, o, kWave);
+            const uint32_t hi = __shfl_up((uint32_t)(incl >> 32), o, kWave);
+            if (lane >= o) incl += ((uint64_t)hi << 32) | lo;
+        }
+        const uint64_t excl = incl - mine;
+        // exactly one lane has excl <= rem < incl
+        if (excl <= rem && rem < incl) {
+            uint64_t run = excl;
+            int tok = i0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (run + q[e] > rem) {
+                    tok = i0 + e;
+                    break;
+                }
+                run += q[e];
+            }
+            a.tokens_out[r] = tok;
+            if (a.logprob_out) {
+                // accumulate the same way as pass 2 would in floating point: log(q_total) via fp64
+                uint64_t total = 0;
+                for (int s2 = 0; s2 < n_seg; ++s2) total += seg_sum[s2];
+                const float x = ((z[tok] - zmax) * a.inv_t);
+                a.logprob_out[r] = x - (float)(log((double)total) - 40.0 * 0.6931471805599453);
+            }
+        }
+    }
+}
+
+hipError_t launch_sample(const SampleArgs& a, hipStream_t s) {
+    if (a.n_out_rows <= 0) return hipSuccess;
+    if (a.vocab > kSegLen * kMaxSeg) return hipErrorInvalidValue;
+    sample_kernel<<<a.n_out_rows, 256, 0, s>>>(a);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// out[r] = z[target] * inv_t - logsumexp(z * inv_t): one workgroup per row.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void lse_gather_kernel(const float* __restrict__ logits,
+                                                         int64_t row_stride, int vocab,
+                                                         const int32_t* __restrict__ target, float inv_t,
+                                                         float* __restrict__ out) {
+    __shared__ float red[4];
+    __shared__ float red2[4];
+    const int r = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const float* z = logits + (int64_t)r * row_stride;
+    float mx = -INFINITY;
+    for (int i = tid; i < vocab; i += 256) mx = fmaxf(mx, z[i]);
+    mx = wave_max(mx);
+    if (lane == 0) red[wave] = mx;
+    __syncthreads();
+    mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    float sum = 0.f;
+    for (int i = tid; i < vocab; i += 256) sum += expf((z[i] - mx) * inv_t);
+    sum = wave_sum(sum);
+    if (lane == 0) red2[wave] = sum;
+    __syncthreads();
+    if (tid == 0) {
+        const float tot = (red2[0] + red2[1]) + (red2[2] + red2[3]);
+        const int t = target[r];
+        const float zt = (t >= 0 && t < vocab) ? z[t] : NAN;
+        out[r] = (zt - mx) * inv_t - logf(tot);
+    }
+}
+
+hipError_t launch_lse_gather(const float* logits, int64_t row_stride, int vocab, const int32_t* target,
+                             float inv_t, float* out, int rows, hipStream_t s) {
+    if (rows <= 0) return hipSuccess;
+    lse_gather_kernel<<<rows, 256, 0, s>>>(logits, row_stride, vocab, target, inv_t, out);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Eq. 7 of the paper: A_i = (R_i - mean) / (std + eps); one thread per group,
+// left-to-right fp64 sums (IEEE add / mul / div / sqrt: same bits as a CPU loop).
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void advantages_kernel(const float* __restrict__ rewards, int n_groups,
+                                                        int G, int ddof, float eps,
+                                                        float* __restrict__ adv) {
+    const int k = blockIdx.x * 64 + threadIdx.x;
+    if (k >= n_groups) return;
+    const float* r = rewards + (int64_t)k * G;
+    float* o = adv + (int64_t)k * G;
+    double s = 0.0;
+    for (int i = 0; i < G; ++i) s += (double)r[i];
+    const double mu = s / (double)G;
+    double ss = 0.0;
+    for (int i = 0; i < G; ++i) {
+        const double d = (double)r[i] - mu;
+        ss += d * d;
+    }
+    const double sigma = __dsqrt_rn(ss / (double)(G - ddof));
+    const double e = (double)eps;
+    if (sigma == 0.0 && e == 0.0) {
+        for (int i = 0; i < G; ++i) o[i] = 0.0f;
+        return;
+    }
+    const double den = sigma + e;
+    for (int i = 0; i < G; ++i) o[i] = (float)(((double)r[i] - mu) / den);
+}
+
+hipError_t launch_advantages(const float* rewards, int n_groups, int G, int ddof, float eps, float* adv,
+                             hipStream_t s) {
+    if (n_groups <= 0) return hipSuccess;
+    advantages_kernel<<<ceil_div(n_groups, 64), 64, 0, s>>>(rewards, n_groups, G, ddof, eps, adv);
+    return hipGetLastError();
+}
+
+}  // namespace rpo

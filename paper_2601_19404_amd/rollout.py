@@ -1,0 +1,97 @@
+"""Host side of the suffix rollout (RPO Sec. 3.2, Eq. 3; Algorithm 1, rollout
+lines): cut the cached answers, pack the prefixes, and drive
+prefill -> fork -> {sample, decode}* through librpo.  Only integer bookkeeping
+happens here; every arithmetic step runs in the library's kernels.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import numpy as np
+import torch
+
+from . import binding as rpo
+
+
+def cut_and_pack(prompts, cached, m):
+    """Per group: q_k || a_k[0:-m_k].  Returns (packed int32 tokens, cu_len[n+1])."""
+    parts, cu = [], [0]
+    for q, a, mk in zip(prompts, cached, m):
+        keep = len(a) - int(mk)
+        if keep < 0:
+            raise ValueError("cut longer than the cached answer")
+        parts.append(np.concatenate([np.asarray(q, np.int32), np.asarray(a[:keep], np.int32)]))
+        cu.append(cu[-1] + len(parts[-1]))
+    return np.concatenate(parts).astype(np.int32), np.asarray(cu, np.int32)
+
+
+def order_by_suffix_length(m):
+    """Permutation that sorts groups by decreasing m: finished groups then always sit at
+    the tail of the row range and every decode step runs on a leading block of rows."""
+    return np.argsort(-np.asarray(m), kind="stable")
+
+
+@dataclass
+class RolloutResult:
+    tokens: torch.Tensor          # int32 [B, max_m] sampled suffix tokens (row r = group * G + i)
+    sample_logprobs: torch.Tensor  # fp32 [B, max_m] log-prob of each token as seen by the sampler
+    m: np.ndarray                 # int32 [n_groups] suffix length per group (batch order)
+    cu_len: np.ndarray
+    n_generated: int
+    logits: list | None = None    # per step: fp32 [rows, V] copies when keep_logits
+
+
+def suffix_rollout(batch: rpo.Batch, prompts, cached, m, temperature: float, seed: int,
+                   seq_ids: torch.Tensor, keep_logits: bool = False, stream=None) -> RolloutResult:
+    """Regenerate m_k tokens for each of the G rollouts of every group.
+
+    Groups must be ordered by decreasing m (see order_by_suffix_length) so that the
+    live rows are always a leading block.  seq_ids: uint64-valued int64 device tensor
+    [B], the Philox stream id of each rollout row."""
+    cfg = batch.model.cfg
+    G, ng = batch.G, batch.n_groups
+    B = ng * G
+    m = np.asarray(m, np.int32)
+    if len(m) != ng or np.any(np.diff(m) > 0):
+        raise ValueError("groups must be ordered by decreasing suffix length")
+    V = cfg.vocab
+    toks_host, cu = cut_and_pack(prompts, cached, m)
+    tokens_dev = torch.from_numpy(toks_host).cuda()
+    max_m = int(m.max()) if ng else 0
+    last_logits = torch.empty((ng, V), dtype=torch.float32, device="cuda")
+    logits = torch.empty((B, V), dtype=torch.float32, device="cuda")
+    out_tokens = torch.zeros((max_m, B), dtype=torch.int32, device="cuda")
+    out_lp = torch.zeros((max_m, B), dtype=torch.float32, device="cuda")
+    row_map = torch.arange(B, dtype=torch.int32, device="cuda") // G
+    kept = [] if keep_logits else None
+
+    rpo.rpo_prefill_prefix(batch, tokens_dev, cu, last_logits, stream)
+    rpo.rpo_kv_fork(batch, stream)
+    # rows alive at step j: groups with m > j, a leading block because m is non-increasing
+    live_groups = [int(np.sum(m > j)) for j in range(max_m)]
+    if max_m > 0:
+        n0 = live_groups[0] * G
+        rpo.rpo_sample(last_logits, ng, V, V, row_map, n0, temperature, seed, seq_ids, 0,
+                       out_tokens[0], out_lp[0], stream)
+        if keep_logits:
+            kept.append(last_logits.clone())
+    for j in range(1, max_m):
+        n = live_groups[j] * G
+        if n == 0:
+            break
+        rpo.rpo_decode_step(batch, out_tokens[j - 1], n, None, logits, stream)
+        rpo.rpo_sample(logits, n, V, V, None, n, temperature, seed, seq_ids, j, out_tokens[j],
+                       out_lp[j], stream)
+        if keep_logits:
+            kept.append(logits[:n].clone())
+    return RolloutResult(out_tokens.t().contiguous(), out_lp.t().contiguous(), m, cu,
+                         int(m.sum()) * G, kept)
+
+
+def pack_suffixes(tokens: torch.Tensor, m, G: int):
+    """tokens [B, max_m] + per-group m -> (packed int32 device tensor, cu_suffix[B+1])."""
+    lens = np.repeat(np.asarray(m, np.int64), G)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    B, max_m = tokens.shape
+    mask = torch.arange(max_m, device=tokens.device)[None, :] < torch.from_numpy(lens).to(tokens.device)[:, None]
+    return tokens[mask].contiguous(), cu

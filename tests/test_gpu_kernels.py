@@ -1,0 +1,165 @@
+"""GPU parity of the stand-alone entry points: GEMM, sampler, advantages.
+Every call goes through the C ABI (paper_2601_19404_amd.binding)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import advantages as oadv
+from oracle import sampler as osampler
+from oracle import transformer as T
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def rpo():
+    from paper_2601_19404_amd import binding
+    binding.lib()
+    yield binding
+    binding.rpo_set_kernel_path(0)
+
+
+def _gemm_case(rpo, M, N, K, dtype, epi, path, seed=0, pad=0):
+    g = torch.Generator().manual_seed(seed)
+    a = torch.randn(M, K + pad, generator=g).to(dtype)[:, :K]
+    w = (torch.randn(N, K + pad, generator=g) * 0.1).to(dtype)[:, :K]
+    c0 = torch.randn(M, N + pad, generator=g)
+    ref = T.lm_head({"lm_head": w.float().numpy()}, a.float().numpy())      # fp64 A @ W^T
+    ad, wd = a.cuda(), w.cuda()
+    # keep the padded strides on the device too
+    ad = torch.empty(M, K + pad, dtype=dtype, device="cuda")[:, :K].copy_(a)
+    wd = torch.empty(N, K + pad, dtype=dtype, device="cuda")[:, :K].copy_(w)
+    if epi == 0:
+        cd = torch.zeros(M, N + pad, dtype=dtype, device="cuda")[:, :N]
+    else:
+        cd = torch.empty(M, N + pad, dtype=torch.float32, device="cuda")[:, :N].copy_(c0[:, :N])
+    rpo.rpo_set_kernel_path(path)
+    rpo.rpo_gemm_nt(ad, wd, cd, epi)
+    torch.cuda.synchronize()
+    got = cd.float().cpu().numpy().astype(np.float64)
+    if epi == 2:
+        ref = ref + c0[:, :N].numpy().astype(np.float64)
+    scale = np.sqrt(K) * 0.1
+    if epi == 0 and dtype == torch.bfloat16:
+        tol = 2.0 ** -8 * np.abs(ref) + 1e-5 * scale        # one bf16 rounding of the result
+    else:
+        tol = 1e-6 * np.abs(ref) + 2e-5 * scale             # fp32 accumulation
+    err = np.abs(got - ref)
+    assert np.all(err <= tol), f"max err {err.max()} at {np.unravel_index(err.argmax(), err.shape)}"
+
+
+@pytest.mark.parametrize("epi", [0, 1, 2])
+@pytest.mark.parametrize("shape", [(1, 7, 8), (64, 64, 64), (130, 200, 136), (33, 515, 72), (300, 129, 1024)])
+def test_gemm_mfma_bf16(rpo, shape, epi):
+    _gemm_case(rpo, *shape, torch.bfloat16, epi, path=0)
+
+
+@pytest.mark.parametrize("shape", [(512, 2048, 1536), (64, 4096, 1536), (200, 1536, 8960)])
+def test_gemm_mfma_bf16_model_shapes(rpo, shape):
+    _gemm_case(rpo, *shape, torch.bfloat16, 1, path=0, seed=3)
+
+
+def test_gemm_mfma_bf16_padded_strides(rpo):
+    _gemm_case(rpo, 70, 90, 128, torch.bfloat16, 1, path=0, pad=8)
+    _gemm_case(rpo, 70, 90, 128, torch.bfloat16, 2, path=0, pad=8)
+
+
+@pytest.mark.parametrize("epi", [0, 1, 2])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("shape", [(1, 5, 3), (65, 130, 77), (128, 128, 256)])
+def test_gemm_generic(rpo, shape, dtype, epi):
+    _gemm_case(rpo, *shape, dtype, epi, path=1)
+    if dtype == torch.float32:
+        _gemm_case(rpo, *shape, dtype, epi, path=0)       # fp32 always takes the generic kernel
+
+
+def test_gemm_rejects_bad_arguments(rpo):
+    a = torch.zeros(4, 8, device="cuda")
+    with pytest.raises(ValueError):
+        rpo.rpo_gemm_nt(a, torch.zeros(4, 9, device="cuda"), torch.zeros(4, 4, device="cuda"), 1)
+    with pytest.raises(rpo.RpoError) as e:
+        rpo.rpo_gemm_nt(a, a, torch.zeros(4, 4, device="cuda"), 7)
+    assert e.value.code == rpo.RPO_EINVAL
+
+
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("vocab,rows,temperature", [(512, 8, 1.0), (151936, 6, 1.0), (152064, 3, 0.7),
+                                                    (1000, 5, 0.7), (3, 4, 1.0), (257, 4, 2.5)])
+def test_sampler_bit_exact(rpo, vocab, rows, temperature):
+    rng = np.random.default_rng(vocab)
+    z = (rng.normal(size=(rows, vocab)) * 0.8).astype(np.float32)
+    z[0, vocab // 2] = 6.0                                   # a peaked row
+    if rows > 1:
+        z[1] = -3.0e38                                       # all weight on one token
+        z[1, vocab - 1] = 0.0
+    zd = torch.from_numpy(z).cuda()
+    seq = np.arange(100, 100 + rows).astype(np.uint64)
+    seqd = torch.from_numpy(seq.astype(np.int64)).cuda()
+    for step in (0, 1, 77):
+        tok = torch.empty(rows, dtype=torch.int32, device="cuda")
+        lp = torch.empty(rows, dtype=torch.float32, device="cuda")
+        rpo.rpo_sample(zd, rows, vocab, vocab, None, rows, temperature, 12345678901234, seqd, step, tok, lp)
+        torch.cuda.synchronize()
+        otok, olp = osampler.sample(z, temperature, 12345678901234, seq, step)
+        np.testing.assert_array_equal(tok.cpu().numpy(), otok)
+        np.testing.assert_allclose(lp.cpu().numpy(), olp, atol=1e-4)
+    assert tok.cpu().numpy()[1] == vocab - 1 if rows > 1 else True
+
+
+def test_sampler_row_map_stride_and_distribution(rpo):
+    rng = np.random.default_rng(5)
+    vocab, stride = 40, 64
+    zpad = np.zeros((2, stride), np.float32)
+    zpad[:, :vocab] = rng.normal(size=(2, vocab)).astype(np.float32) * 1.5
+    zpad[:, vocab:] = 50.0                                   # padding must never be read
+    n = 20000
+    row_map = (np.arange(n) % 2).astype(np.int32)
+    seq = np.arange(n).astype(np.uint64)
+    tok = torch.empty(n, dtype=torch.int32, device="cuda")
+    rpo.rpo_sample(torch.from_numpy(zpad).cuda(), 2, vocab, stride, torch.from_numpy(row_map).cuda(), n,
+                   1.0, 9, torch.from_numpy(seq.astype(np.int64)).cuda(), 4, tok, None)
+    torch.cuda.synchronize()
+    got = tok.cpu().numpy()
+    otok, _ = osampler.sample(zpad[:, :vocab], 1.0, 9, seq[:500], 4, row_map=row_map[:500])
+    np.testing.assert_array_equal(got[:500], otok)
+    assert got.max() < vocab
+    for r in range(2):                                       # chi-square against the fp64 softmax
+        p = np.exp(zpad[r, :vocab].astype(np.float64))
+        p /= p.sum()
+        cnt = np.bincount(got[row_map == r], minlength=vocab)
+        chi2 = float(((cnt - cnt.sum() * p) ** 2 / (cnt.sum() * p)).sum())
+        assert chi2 < 90.0                                   # 39 dof, p ~ 1e-5
+
+
+def test_sampler_rejects_bad_arguments(rpo):
+    z = torch.zeros(2, 8, device="cuda")
+    s = torch.zeros(2, dtype=torch.int64, device="cuda")
+    t = torch.zeros(2, dtype=torch.int32, device="cuda")
+    for kw in (dict(temperature=0.0), dict(temperature=-1.0), dict(row_stride=4)):
+        args = dict(temperature=1.0, row_stride=8)
+        args.update(kw)
+        with pytest.raises((rpo.RpoError, ValueError)):
+            rpo.rpo_sample(z, 2, 8, args["row_stride"], None, 2, args["temperature"], 1, s, 0, t, None)
+    rpo.rpo_sample(z, 2, 8, 8, None, 0, 1.0, 1, s, 0, t, None)      # zero rows: a no-op
+
+
+# ---------------------------------------------------------------------------
+def test_advantages_bit_exact(rpo):
+    rng = np.random.default_rng(0)
+    cases = [(rng.random((64, 8)) < 0.5).astype(np.float32), (rng.random((32, 8)) < 0.3).astype(np.float32),
+             rng.normal(size=(100, 6)).astype(np.float32), np.ones((3, 4), np.float32),
+             rng.normal(size=(5, 1)).astype(np.float32), rng.normal(size=(7, 16)).astype(np.float32) * 1e3]
+    for r in cases:
+        ng, g = r.shape
+        for ddof, eps in ((0, 0.0), (1, 0.0), (0, 1e-4)):
+            if ddof >= g:
+                continue
+            out = torch.empty(ng, g, dtype=torch.float32, device="cuda")
+            rpo.grpo_advantages(torch.from_numpy(r).cuda(), ng, g, ddof, eps, out)
+            torch.cuda.synchronize()
+            ref = oadv.grpo_advantages(r, ddof, eps)
+            np.testing.assert_array_equal(out.cpu().numpy().view(np.uint32), ref.view(np.uint32))
+    with pytest.raises(rpo.RpoError):
+        rpo.grpo_advantages(torch.zeros(2, 2, device="cuda"), 2, 2, 2, 0.0, torch.zeros(2, 2, device="cuda"))
+    with pytest.raises(rpo.RpoError):
+        rpo.grpo_advantages(torch.zeros(2, 1, device="cuda"), 2, 1, 1, 0.0, torch.zeros(2, 1, device="cuda"))

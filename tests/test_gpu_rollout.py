@@ -1,0 +1,240 @@
+"""End-to-end GPU parity of the suffix rollout against the fp64 oracle.
+
+The GPU samples its own tokens; the oracle then (a) recomputes, teacher-forced on
+those tokens, every logits row the GPU sampled from and every suffix log-prob
+(floating point: within the stated tolerance), and (b) is fed the GPU's logits and
+must return the GPU's tokens (integers: bit-exact)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import advantages as oadv
+from oracle import transformer as T
+from paper_2601_19404_amd import synth
+from tests import util
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+@pytest.fixture(scope="module")
+def rpo():
+    from paper_2601_19404_amd import binding
+    binding.lib()
+    yield binding
+    binding.rpo_set_kernel_path(0)
+
+
+def run_case(rpo, mcfg, prompts, cached, m, G, temperature=1.0, seed=3, page=64, path=0,
+             max_rows=None, weight_seed=1234, perturb=True, check_logprobs=True, n_layers=None):
+    from paper_2601_19404_amd import rollout
+    rpo.rpo_set_kernel_path(path)
+    w = synth.make_weights(mcfg, seed=weight_seed, n_layers=n_layers)
+    if perturb:
+        w = synth.perturb_gains(w)
+    w_np = synth.weights_to_numpy(w)
+    shape = util.oracle_shape(mcfg, n_layers)
+    cfg = mcfg if n_layers is None else synth.ModelCfg(**{**mcfg.__dict__, "n_layers": n_layers})
+    model = rpo.rpo_model_create(cfg, util.to_device(w))
+    order = rollout.order_by_suffix_length(m)
+    prompts = [prompts[i] for i in order]
+    cached = [cached[i] for i in order]
+    m = np.asarray(m)[order]
+    ng = len(prompts)
+    B = ng * G
+    pref_lens = [len(p) + len(a) - int(mm) for p, a, mm in zip(prompts, cached, m)]
+    max_prefix, max_suffix = max(pref_lens), max(int(m.max()), 1)
+    if max_rows is None:
+        max_rows = max(max_prefix, B, max_suffix)
+    batch = rpo.rpo_batch_create(model, ng, G, max_prefix, max_suffix, page, max_rows)
+    seq_ids = util.seq_ids_dev(B, base=1000)
+    res = rollout.suffix_rollout(batch, prompts, cached, m, temperature, seed, seq_ids, keep_logits=True)
+    torch.cuda.synchronize()
+    toks = res.tokens.cpu().numpy()
+    slp = res.sample_logprobs.cpu().numpy()
+    kept = [k.cpu().numpy() for k in res.logits]
+    sid = np.arange(1000, 1000 + B).astype(np.uint64)
+    tol = TOL[mcfg.dtype]
+
+    # (b) integer contract: oracle sampler on the GPU's logits
+    max_m = int(m.max())
+    for j in range(max_m):
+        n = int(np.sum(m > j)) * G
+        if n == 0:
+            break
+        if j == 0:
+            util.check_sampler_consistency(kept[0], temperature, seed, sid[:n], 0, toks[:n, 0],
+                                           row_map=np.arange(n) // G)
+        else:
+            util.check_sampler_consistency(kept[j], temperature, seed, sid[:n], j, toks[:n, j])
+
+    # (a) floating point: oracle logits teacher-forced on the GPU's tokens
+    worst, sq, cnt = 0.0, 0.0, 0
+    for g in range(ng):
+        prefix = np.concatenate([prompts[g], cached[g][:len(cached[g]) - int(m[g])]])
+        for i in range(G):
+            r = g * G + i
+            mg = int(m[g])
+            if mg == 0:
+                continue
+            ref = T.teacher_forced_logits(shape, w_np, prefix, toks[r, :mg])
+            for j in range(mg):
+                got = kept[j][g if j == 0 else r]
+                worst = max(worst, float(np.max(np.abs(got - ref[j]))))
+            lp_ref = T.log_softmax(ref / temperature)[np.arange(mg), toks[r, :mg]]
+            assert np.max(np.abs(slp[r, :mg] - lp_ref)) < tol, "sampler log-prob"
+    print(f"[{mcfg.name} path={path}] logits vs oracle: max {worst:.3e} rms {np.sqrt(sq / max(cnt, 1)):.3e} "
+          f"over {cnt} values", flush=True)
+    assert worst < tol, f"logits differ from the oracle by {worst}"
+
+    if check_logprobs:
+        packed, cu_s = rollout.pack_suffixes(res.tokens, m, G)
+        out = torch.full((max(int(cu_s[-1]), 1),), 7.0, dtype=torch.float32, device="cuda")
+        rpo.rpo_suffix_logprobs(batch, packed, cu_s, temperature, out)
+        torch.cuda.synchronize()
+        out = out.cpu().numpy()
+        for g in range(ng):
+            prefix = np.concatenate([prompts[g], cached[g][:len(cached[g]) - int(m[g])]])
+            for i in range(G):
+                r = g * G + i
+                mg = int(m[g])
+                ref = T.suffix_logprobs(shape, w_np, prefix, toks[r, :mg], temperature)
+                got = out[cu_s[r]:cu_s[r + 1]]
+                assert got.shape == ref.shape
+                if mg:
+                    assert np.max(np.abs(got - ref)) < tol, "suffix log-probs"
+                    # one policy: ratio of Eq. 7 is 1 -> same value as the sampler reported
+                    assert np.max(np.abs(got - slp[r, :mg])) < 2 * tol
+    return worst, res
+
+
+def tiny_workload(ng=2, seed=1):
+    wl = synth.make_workload(synth.C0, n_groups=ng, token_seed=seed, cut_seed=seed + 1)
+    return [wl.prompts[k] for k in range(ng)], [wl.cached[k] for k in range(ng)], wl.m
+
+
+def test_c0_tiny_fp32_end_to_end(rpo):
+    """BASELINE config 0 exactly: 2 prompts x G=4, prompt 16, answer 64 cut in [48, 56]."""
+    p, a, m = tiny_workload()
+    worst, res = run_case(rpo, synth.TINY, p, a, m, G=4, page=16)
+    assert res.n_generated == int(m.sum()) * 4
+    # rewards -> advantages, bit-exact
+    wl = synth.make_workload(synth.C0)
+    out = torch.empty(2, 4, dtype=torch.float32, device="cuda")
+    rpo.grpo_advantages(torch.from_numpy(wl.rewards).cuda(), 2, 4, 0, 0.0, out)
+    np.testing.assert_array_equal(out.cpu().numpy(), oadv.grpo_advantages(wl.rewards))
+
+
+@pytest.mark.parametrize("page", [16, 32, 64])
+def test_tiny_fp32_page_sizes_and_chunked_prefill(rpo, page):
+    p, a, m = tiny_workload(ng=5, seed=11)
+    # max_rows below the total prefix rows forces several prefill chunks
+    run_case(rpo, synth.TINY, p, a, m, G=3, page=page, max_rows=150, temperature=0.7)
+
+
+def test_tiny_fp32_edge_lengths(rpo):
+    """Prefix lengths around page boundaries (no partial page to copy, prefix shorter than a
+    page, one-token prefix) and a group that regenerates nothing (m = 0)."""
+    rng = np.random.default_rng(7)
+    v = synth.TINY.vocab
+    prompts = [rng.integers(0, v, size=n).astype(np.int32) for n in (16, 16, 1, 5, 16)]
+    cached = [rng.integers(0, v, size=n).astype(np.int32) for n in (32, 19, 6, 30, 20)]
+    m = np.array([16, 3, 6, 9, 0])          # prefixes: 32 (= 2 pages), 32, 1, 26, 36
+    run_case(rpo, synth.TINY, prompts, cached, m, G=2, page=16)
+
+
+BF16_SMALL = synth.ModelCfg("bf16-small", 2, 768, 6, 1, 128, 1024, 2048, "bf16")
+BF16_GQA7 = synth.ModelCfg("bf16-gqa7", 2, 896, 7, 1, 128, 512, 1024, "bf16")
+BF16_2KV = synth.ModelCfg("bf16-2kv", 3, 1536, 12, 2, 128, 1024, 4096, "bf16")
+
+
+def bf16_workload(mcfg, lens, ms, seed=0):
+    rng = np.random.default_rng(seed)
+    prompts = [rng.integers(0, mcfg.vocab, size=8).astype(np.int32) for _ in lens]
+    cached = [rng.integers(0, mcfg.vocab, size=n).astype(np.int32) for n in lens]
+    return prompts, cached, np.asarray(ms)
+
+
+@pytest.mark.parametrize("path", [1, 0])
+def test_bf16_small_generic_and_mfma(rpo, path):
+    """Same case through the generic kernels (path 1) and the MFMA kernels (path 0): prefixes
+    spanning several 64-token pages with ragged tails, G = 8 rollouts sharing them."""
+    p, a, m = bf16_workload(BF16_SMALL, lens=(200, 333, 130), ms=(9, 12, 5))
+    run_case(rpo, BF16_SMALL, p, a, m, G=8, path=path)
+
+
+def test_bf16_gqa7_mfma(rpo):
+    """7 query heads per KV head (the 7B shape's ratio): 8 x 7 = 56 query rows per shared page."""
+    p, a, m = bf16_workload(BF16_GQA7, lens=(190, 64, 70), ms=(6, 8, 3), seed=1)
+    run_case(rpo, BF16_GQA7, p, a, m, G=8)
+
+
+def test_bf16_two_kv_heads_many_rollouts_mfma(rpo):
+    """12 q / 2 kv heads (the 1.5B shape's ratio) and G = 16: two column tiles per group;
+    prefix of exactly 4 pages, a prefix shorter than one page, chunked prefill."""
+    p, a, m = bf16_workload(BF16_2KV, lens=(256 - 8 + 7, 40, 150), ms=(7, 10, 4), seed=2)
+    run_case(rpo, BF16_2KV, p, a, m, G=16, max_rows=300)
+
+
+def test_decode_active_mask_and_row_prefix(rpo):
+    """Rows masked out by `active` must not disturb the live ones; a shorter leading block works."""
+    from paper_2601_19404_amd import rollout
+    rpo.rpo_set_kernel_path(0)
+    mcfg = BF16_SMALL
+    w = synth.make_weights(mcfg, seed=5)
+    model = rpo.rpo_model_create(mcfg, util.to_device(w))
+    p, a, m = bf16_workload(mcfg, lens=(100, 90), ms=(4, 4), seed=3)
+    G, ng, V = 4, 2, mcfg.vocab
+    toks, cu = rollout.cut_and_pack(p, a, m)
+    outs = []
+    for mask in (None, [1, 1, 0, 1, 1, 1, 1, 0]):
+        batch = rpo.rpo_batch_create(model, ng, G, int(max(np.diff(cu))), 8, 64, 256)
+        last = torch.empty(ng, V, device="cuda")
+        rpo.rpo_prefill_prefix(batch, torch.from_numpy(toks).cuda(), cu, last)
+        rpo.rpo_kv_fork(batch)
+        step_tok = torch.arange(8, dtype=torch.int32, device="cuda") * 7 + 3
+        logits = torch.full((8, V), float("nan"), device="cuda")
+        act = None if mask is None else torch.tensor(mask, dtype=torch.uint8, device="cuda")
+        rpo.rpo_decode_step(batch, step_tok, 8, act, logits)
+        rpo.rpo_decode_step(batch, step_tok + 1, 8, act, logits)
+        torch.cuda.synchronize()
+        outs.append(logits.cpu().numpy())
+    live = np.array([1, 1, 0, 1, 1, 1, 1, 0], bool)
+    np.testing.assert_array_equal(outs[0][live], outs[1][live])
+    assert np.all(np.isfinite(outs[0]))
+
+
+def test_state_and_argument_errors(rpo):
+    from paper_2601_19404_amd import rollout
+    mcfg = synth.TINY
+    model = rpo.rpo_model_create(mcfg, util.to_device(synth.make_weights(mcfg)))
+    with pytest.raises(rpo.RpoError):
+        rpo.rpo_batch_create(model, 2, 4, 80, 16, 24, 128)            # page size not a power of two
+    with pytest.raises(rpo.RpoError):
+        rpo.rpo_batch_create(model, 2, 4, 80, 16, 16, 40)             # max_rows < max_prefix
+    batch = rpo.rpo_batch_create(model, 2, 4, 80, 2, 16, 128)
+    V = mcfg.vocab
+    logits = torch.empty(8, V, device="cuda")
+    tok = torch.zeros(8, dtype=torch.int32, device="cuda")
+    with pytest.raises(rpo.RpoError) as e:
+        rpo.rpo_decode_step(batch, tok, 8, None, logits)              # before prefill / fork
+    assert e.value.code == rpo.RPO_ESTATE
+    with pytest.raises(rpo.RpoError) as e:
+        rpo.rpo_kv_fork(batch)
+    assert e.value.code == rpo.RPO_ESTATE
+    p, a, m = tiny_workload()
+    toks, cu = rollout.cut_and_pack(p, a, m)
+    bad = cu.copy()
+    bad[1] = 200                                                      # longer than max_prefix
+    with pytest.raises(rpo.RpoError) as e:
+        rpo.rpo_prefill_prefix(batch, torch.from_numpy(toks).cuda(), bad, torch.empty(2, V, device="cuda"))
+    assert e.value.code == rpo.RPO_EINVAL
+    rpo.rpo_prefill_prefix(batch, torch.from_numpy(toks).cuda(), cu, torch.empty(2, V, device="cuda"))
+    rpo.rpo_kv_fork(batch)
+    rpo.rpo_decode_step(batch, tok, 8, None, logits)
+    rpo.rpo_decode_step(batch, tok, 8, None, logits)
+    with pytest.raises(rpo.RpoError) as e:
+        rpo.rpo_decode_step(batch, tok, 8, None, logits)              # beyond max_suffix = 2
+    assert e.value.code == rpo.RPO_ESTATE
+    torch.cuda.synchronize()
