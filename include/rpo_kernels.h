@@ -8,6 +8,7 @@
 #ifndef RPO_KERNELS_H
 #define RPO_KERNELS_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -19,16 +20,39 @@ extern "C" {
  *   a_dev  device, [M, K] row-major, row stride lda (elements), dtype RPO_F32 / RPO_BF16
  *   w_dev  device, [N, K] row-major, row stride ldw, same dtype
  *   c_dev  device, [M, N] row-major, row stride ldc
- *   epilogue 0: C = result in `dtype`; 1: C = result as fp32; 2: C (fp32) += result
+ *   epilogue 0: C = result in `dtype`; 1: C = result as fp32; 2: C (fp32) += result;
+ *            3: SwiGLU: W rows are [gate (F rows); up (F rows)], N = 2F, and
+ *               C[M, F] = silu(A Wgate^T) * (A Wup^T) in `dtype` (ldc >= F)
+ *   ws_dev   device scratch for K-split partial sums, ws_bytes long, or NULL / 0: skinny
+ *            problems are then not split along K (same result, fewer busy CUs)
  * bf16 operands with K, lda, ldw multiples of 8 and 16-byte aligned bases run on the
- * matrix cores; anything else on the generic kernel.  Errors: RPO_EINVAL, RPO_EHIP. */
+ * matrix cores (SwiGLU also needs F a multiple of 32); anything else on the generic
+ * kernel.  Errors: RPO_EINVAL, RPO_EHIP. */
 int rpo_gemm_nt(const void *a_dev, int64_t lda, const void *w_dev, int64_t ldw, void *c_dev, int64_t ldc,
-                int32_t M, int32_t N, int32_t K, int32_t dtype, int32_t epilogue, void *stream);
+                int32_t M, int32_t N, int32_t K, int32_t dtype, int32_t epilogue, void *ws_dev,
+                size_t ws_bytes, void *stream);
 
 /* Process-wide kernel selection: 0 = fastest available kernel for the shape (default),
  * 1 = generic vector-ALU kernels for GEMM and attention regardless of shape.
  * Not thread-safe against concurrent compute calls.  Errors: RPO_EINVAL. */
 int rpo_set_kernel_path(int path);
+
+/* Per-kernel timing for roofline reports.  rpo_profile_start(kernel_id) makes every later
+ * launch of that kernel (process-wide, any stream) bracketed by a pair of HIP events recorded
+ * on the launch stream; rpo_profile_stop waits for the last event and returns the number of
+ * launches, the summed event time in milliseconds, and the summed ALGORITHMIC flops and bytes
+ * of those launches as the library counts them (GEMM: 2MNK flops, operands + result bytes;
+ * decode attention: K/V bytes with a group's shared prefix counted once per group; sampler:
+ * the logits rows read once).  Kernel ids:
+ *   1  gemm_mfma_kernel<256,256,2,2,..> (M > 512)    2  gemm_mfma_kernel<256,128,2,2,..> (M <= 512)
+ *   3  gemm_mfma_kernel<128,128,2,2,..> (M <= 128)   4  gemm_mfma_kernel<64,128,1,2,..>  (M <= 64)
+ *      (all epilogues of a tile shape together; a K-split launch includes its reduction)
+ *   7  gemm_generic_kernel      8  attn_decode_mfma_kernel (+ merge)   9  attn_chunk_mfma_kernel
+ *   10 sample_kernel
+ * Host-side only (event create / record / synchronise); not thread-safe.
+ * Errors: RPO_EINVAL (unknown id, NULL), RPO_EHIP. */
+int rpo_profile_start(int kernel_id);
+int rpo_profile_stop(int64_t *n_launches, double *total_ms, double *total_flops, double *total_bytes);
 
 #ifdef __cplusplus
 }

@@ -70,11 +70,14 @@ def lib() -> C.CDLL:
     L.rpo_sample.argtypes = [vp, i32, i32, i64, vp, i32, f32, u64, vp, u32, vp, vp, vp]
     L.rpo_suffix_logprobs.argtypes = [vp, vp, C.POINTER(i32), f32, vp, vp]
     L.grpo_advantages.argtypes = [vp, i32, i32, i32, f32, vp, vp]
-    L.rpo_gemm_nt.argtypes = [vp, i64, vp, i64, vp, i64, i32, i32, i32, i32, i32, vp]
+    L.rpo_gemm_nt.argtypes = [vp, i64, vp, i64, vp, i64, i32, i32, i32, i32, i32, vp, sz, vp]
     L.rpo_set_kernel_path.argtypes = [C.c_int]
+    L.rpo_profile_start.argtypes = [C.c_int]
+    L.rpo_profile_stop.argtypes = [C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double),
+                                   C.POINTER(C.c_double)]
     for name in ("rpo_model_create", "rpo_batch_create", "rpo_prefill_prefix", "rpo_kv_fork",
                  "rpo_decode_step", "rpo_sample", "rpo_suffix_logprobs", "grpo_advantages",
-                 "rpo_gemm_nt", "rpo_set_kernel_path"):
+                 "rpo_gemm_nt", "rpo_set_kernel_path", "rpo_profile_start", "rpo_profile_stop"):
         getattr(L, name).restype = C.c_int
     _lib = L
     return L
@@ -83,7 +86,8 @@ def lib() -> C.CDLL:
 EXPORTS = ("rpo_model_create", "rpo_model_destroy", "rpo_kv_pool_bytes", "rpo_workspace_bytes",
            "rpo_batch_create", "rpo_batch_destroy", "rpo_prefill_prefix", "rpo_kv_fork",
            "rpo_decode_step", "rpo_sample", "rpo_suffix_logprobs", "grpo_advantages",
-           "rpo_last_error", "rpo_gemm_nt", "rpo_set_kernel_path")
+           "rpo_last_error", "rpo_gemm_nt", "rpo_set_kernel_path", "rpo_profile_start",
+           "rpo_profile_stop")
 
 
 def _check(code: int) -> None:
@@ -259,16 +263,19 @@ def grpo_advantages(rewards_dev: torch.Tensor, n_groups: int, G: int, ddof: int,
 
 
 def rpo_gemm_nt(a_dev: torch.Tensor, w_dev: torch.Tensor, c_dev: torch.Tensor, epilogue: int,
-                stream=None) -> None:
-    """C (op)= A W^T for 2-D tensors (row strides taken from the tensors)."""
+                ws_dev: torch.Tensor | None = None, stream=None) -> None:
+    """C (op)= A W^T for 2-D tensors (row strides taken from the tensors); epilogue 3 is the
+    fused SwiGLU (C is [M, N/2]).  ws_dev: optional uint8 scratch for K-split partial sums."""
     M, K = a_dev.shape
     N, K2 = w_dev.shape
-    if K != K2 or tuple(c_dev.shape) != (M, N) or a_dev.stride(1) != 1 or w_dev.stride(1) != 1 \
+    n_out = N // 2 if epilogue == 3 else N
+    if K != K2 or tuple(c_dev.shape) != (M, n_out) or a_dev.stride(1) != 1 or w_dev.stride(1) != 1 \
             or c_dev.stride(1) != 1:
         raise ValueError("shape / stride mismatch")
     dt = RPO_F32 if a_dev.dtype == torch.float32 else RPO_BF16
     _check(lib().rpo_gemm_nt(a_dev.data_ptr(), a_dev.stride(0), w_dev.data_ptr(), w_dev.stride(0),
-                             c_dev.data_ptr(), c_dev.stride(0), M, N, K, dt, epilogue, _stream(stream)))
+                             c_dev.data_ptr(), c_dev.stride(0), M, N, K, dt, epilogue, _ptr(ws_dev),
+                             0 if ws_dev is None else ws_dev.numel(), _stream(stream)))
 
 
 def rpo_set_kernel_path(path: int) -> None:
@@ -277,3 +284,18 @@ def rpo_set_kernel_path(path: int) -> None:
 
 def rpo_last_error() -> str:
     return lib().rpo_last_error().decode()
+
+
+KERNEL_IDS = {"gemm256": 1, "gemm256x128": 2, "gemm128": 3, "gemm64": 4, "gemm_generic": 7,
+              "attn_decode": 8, "attn_chunk": 9, "sample": 10}
+
+
+def rpo_profile_start(kernel_id: int) -> None:
+    _check(lib().rpo_profile_start(kernel_id))
+
+
+def rpo_profile_stop():
+    """-> (launches, total_ms, total_flops, total_bytes) of the kernel chosen at start."""
+    n, ms, fl, by = C.c_int64(), C.c_double(), C.c_double(), C.c_double()
+    _check(lib().rpo_profile_stop(C.byref(n), C.byref(ms), C.byref(fl), C.byref(by)))
+    return n.value, ms.value, fl.value, by.value

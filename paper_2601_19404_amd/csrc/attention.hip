@@ -145,11 +145,11 @@ __device__ inline void attn_stream_pages(const bf16* qptr, int limit, const bf16
             for (int e = 0; e < 8; ++e) bq[kk][e] = (__bf16)0.0f;
     }
 
-    uint4 rk[4], rv[4];
+    u32x4_t rk[4], rv[4];
     auto load_page = [&](int p) {
         const int64_t page = table[p];
-        const uint4* kb = (const uint4*)(pool + geom.k_block(layer, page, kh));
-        const uint4* vb = (const uint4*)(pool + geom.v_block(layer, page, kh));
+        const u32x4_t* kb = (const u32x4_t*)(pool + geom.k_block(layer, page, kh));
+        const u32x4_t* vb = (const u32x4_t*)(pool + geom.v_block(layer, page, kh));
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             rk[i] = kb[tid + i * 256];
@@ -160,8 +160,8 @@ __device__ inline void attn_stream_pages(const bf16* qptr, int limit, const bf16
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int c = tid + i * 256;
-            *(uint4*)(Ks + buf * kKTile + (c >> 4) * kKRow + (c & 15) * 8) = rk[i];
-            *(uint4*)(Vs + buf * kVTile + (c >> 3) * kVRow + (c & 7) * 8) = rv[i];
+            *(u32x4_t*)(Ks + buf * kKTile + (c >> 4) * kKRow + (c & 15) * 8) = rk[i];
+            *(u32x4_t*)(Vs + buf * kVTile + (c >> 3) * kVRow + (c & 7) * 8) = rv[i];
         }
     };
 
@@ -388,6 +388,8 @@ static bool mfma_attn_ok(const AttnArgs& a) {
     return a.path != 1 && a.dtype == kBF16 && a.dh == kDh && a.geom.page_tokens == kPt && hpk >= 1 &&
            hpk <= 64 && a.q_stride % 8 == 0 && ((uintptr_t)a.q % 16 == 0);
 }
+
+bool attn_uses_mfma(const AttnArgs& a) { return mfma_attn_ok(a); }
 
 static hipError_t set_attn_lds(const void* fn) {
     return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAttnLds);

@@ -8,6 +8,9 @@ namespace rpo {
 
 constexpr int kWave = 64;  // CDNA wavefront width
 
+// 16-byte register value for staging global -> LDS copies (a native vector: stays in VGPRs).
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+
 // bfloat16 as raw bits: conversions are explicit so rounding is always RNE.
 struct bf16 {
     uint16_t bits;

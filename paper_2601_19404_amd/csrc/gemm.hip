@@ -2,8 +2,17 @@
 // the decoder (QKV, O, gate/up, down, LM head).  Both operands are K-contiguous.
 //
 //  * gemm_mfma_kernel: bf16 operands on the CDNA4 matrix cores
-//    (v_mfma_f32_32x32x16_bf16), LDS-staged 64-deep K slabs, double buffered, the
-//    next slab's global loads in flight while the current one is multiplied.
+//    (v_mfma_f32_32x32x16_bf16).  64-deep K slabs are staged through LDS, double
+//    buffered; the next slab's global loads are in flight while the current slab is
+//    multiplied.  Tile shapes: 256x256 (prefill / log-prob passes), 256x128 and
+//    128x128 (decode batches), 64x128 (a handful of rows).  Skinny problems that would
+//    leave most of the 256 CUs idle are split along K; the fp32 partial sums go to a
+//    workspace and gemm_splitk_reduce_kernel applies the epilogue (deterministic: no
+//    floating-point atomics).  Workgroup ids are remapped so that the tiles sharing a
+//    weight tile run on the same XCD (each XCD has its own L2).
+//  * SwiGLU is fused into the gate/up projection: the kernel reads the weight rows in
+//    the order [32 gate | 32 up | 32 gate | ...], so each wave holds matching gate and
+//    up columns in neighbouring accumulator blocks and writes silu(gate) * up directly.
 //  * gemm_generic_kernel: any dtype on the vector ALUs (fp32 tiny model, shapes the
 //    MFMA kernel does not take).
 #include "kernels.hpp"
@@ -12,6 +21,8 @@ namespace rpo {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+__device__ inline float silu_f(float g) { return g / (1.0f + __expf(-g)); }
 
 // ---------------------------------------------------------------------------
 // generic kernel: 64x64 tile, 16-deep slabs, 256 threads, 4x4 outputs per thread
@@ -70,6 +81,26 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const T* __restrict__
     }
 }
 
+// generic SwiGLU projection: act[m, j] = silu(A W_gate^T)[m, j] * (A W_up^T)[m, j]
+template <typename T>
+__global__ __launch_bounds__(256) void gemm_generic_swiglu_kernel(const T* __restrict__ A, int64_t lda,
+                                                                  const T* __restrict__ W, int64_t ldw,
+                                                                  T* __restrict__ C, int64_t ldc, int M,
+                                                                  int F, int K) {
+    const int j = blockIdx.x * 256 + threadIdx.x, m = blockIdx.y;
+    if (j >= F) return;
+    const T* a = A + (int64_t)m * lda;
+    const T* wg = W + (int64_t)j * ldw;
+    const T* wu = W + (int64_t)(F + j) * ldw;
+    float g = 0.f, u = 0.f;
+    for (int k = 0; k < K; ++k) {
+        const float av = to_f32<T>(a[k]);
+        g = fmaf(av, to_f32<T>(wg[k]), g);
+        u = fmaf(av, to_f32<T>(wu[k]), u);
+    }
+    C[(int64_t)m * ldc + j] = from_f32<T>(g / (1.0f + expf(-g)) * u);
+}
+
 // ---------------------------------------------------------------------------
 // MFMA kernel.
 //
@@ -83,63 +114,82 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(const T* __restrict__
 // ---------------------------------------------------------------------------
 constexpr int kBK = 64;
 constexpr int kLdsRow = kBK + 8;
+constexpr int kXcd = 8;  // XCDs of an MI355X; workgroup i is dispatched to XCD i % 8
 
-template <int BM, int BN, int WM, int WN, int EPI>
+// Column n of the (virtual) output -> row of W.  SwiGLU mode interleaves gate and up rows
+// in blocks of 32: virtual columns [64q, 64q+32) are gate rows 32q.., [64q+32, 64q+64) up rows.
+template <bool SWIGLU>
+__device__ inline int weight_row(int n, int F) {
+    if (!SWIGLU) return n;
+    return ((n >> 5) & 1) * F + ((n >> 6) << 5) + (n & 31);
+}
+
+// EPI: kEpiStore / kEpiStoreF32 / kEpiAddF32 / kEpiSwiglu write the result; kEpiPartial writes
+// fp32 partial sums of K-split `blockIdx.y` to Cv[split][M][N].
+template <int BM, int BN, int WM, int WN, int EPI, bool SWIGLU>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_kernel(const bf16* __restrict__ A, int64_t lda,
                                                                 const bf16* __restrict__ W, int64_t ldw,
                                                                 void* __restrict__ Cv, int64_t ldc,
-                                                                int M, int N, int K, int grid_m) {
+                                                                int M, int N, int K, int grid_m, int n_tiles,
+                                                                int k_per_split, int F) {
     constexpr int NT = WM * WN * 64;
     constexpr int TM = BM / WM, TN = BN / WN;
     constexpr int MI = TM / 32, NI = TN / 32;
     constexpr int A_CHUNKS = BM * (kBK / 8) / NT;  // 16-byte pieces per thread and slab
     constexpr int B_CHUNKS = BN * (kBK / 8) / NT;
     static_assert(BM * (kBK / 8) % NT == 0 && BN * (kBK / 8) % NT == 0, "tile/thread mismatch");
+    static_assert(!SWIGLU || NI % 2 == 0, "SwiGLU needs gate/up block pairs inside a wave");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     bf16* As = (bf16*)smem_raw;                 // [2][BM][kLdsRow]
     bf16* Bs = As + 2 * BM * kLdsRow;           // [2][BN][kLdsRow]
 
-    // Consecutive workgroups walk down M first: the (few) row tiles that share one
-    // weight tile run back to back, so the weight tile is fetched from HBM once.
-    const int bm = blockIdx.x % grid_m, bn = blockIdx.x / grid_m;
+    // Tile order: ids handed to one XCD (i % 8 == x) form one contiguous run of logical tiles,
+    // and logical tiles walk down M first, so the row tiles sharing a weight tile hit one L2.
+    const int per_xcd = (n_tiles + kXcd - 1) / kXcd;
+    const int logical = (blockIdx.x % kXcd) * per_xcd + blockIdx.x / kXcd;
+    if (logical >= n_tiles) return;
+    const int bm = logical % grid_m, bn = logical / grid_m;
     const int m0 = bm * BM, n0 = bn * BN;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave % WM, wn = wave / WM;
+    const int k_begin = blockIdx.y * k_per_split;
+    const int k_end = min(K, k_begin + k_per_split);
 
-    uint4 ra[A_CHUNKS], rb[B_CHUNKS];
-    const uint4 zero4 = {0, 0, 0, 0};
+    // Thread t moves the 16-byte piece (row t / 8 + i * NT / 8, k-chunk t % 8) of each slab.
+    constexpr int ROWS_PER_PASS = NT / 8;
+    const int ld_row = tid >> 3, ld_k = (tid & 7) * 8;
+    const bf16* a_base = A + (int64_t)(m0 + ld_row) * lda + ld_k;
+    u32x4_t ra[A_CHUNKS], rb[B_CHUNKS];
+    int64_t b_off[B_CHUNKS];  // weight rows are not an arithmetic sequence in SwiGLU order
+#pragma unroll
+    for (int i = 0; i < B_CHUNKS; ++i) {
+        const int gn = n0 + ld_row + i * ROWS_PER_PASS;
+        b_off[i] = gn < N ? (int64_t)weight_row<SWIGLU>(gn, F) * ldw + ld_k : -1;
+    }
 
-    auto load_slab = [&](int k0) {
-#pragma unroll
-        for (int i = 0; i < A_CHUNKS; ++i) {
-            const int c = tid + i * NT;
-            const int r = c >> 3, kc = (c & 7) * 8;
-            const int gm = m0 + r, gk = k0 + kc;
-            ra[i] = (gm < M && gk < K) ? *(const uint4*)(A + (int64_t)gm * lda + gk) : zero4;
-        }
-#pragma unroll
-        for (int i = 0; i < B_CHUNKS; ++i) {
-            const int c = tid + i * NT;
-            const int r = c >> 3, kc = (c & 7) * 8;
-            const int gn = n0 + r, gk = k0 + kc;
-            rb[i] = (gn < N && gk < K) ? *(const uint4*)(W + (int64_t)gn * ldw + gk) : zero4;
-        }
-    };
-    auto store_slab = [&](int buf) {
-        bf16* as = As + buf * BM * kLdsRow;
-        bf16* bs = Bs + buf * BN * kLdsRow;
-#pragma unroll
-        for (int i = 0; i < A_CHUNKS; ++i) {
-            const int c = tid + i * NT;
-            *(uint4*)(as + (c >> 3) * kLdsRow + (c & 7) * 8) = ra[i];
-        }
-#pragma unroll
-        for (int i = 0; i < B_CHUNKS; ++i) {
-            const int c = tid + i * NT;
-            *(uint4*)(bs + (c >> 3) * kLdsRow + (c & 7) * 8) = rb[i];
-        }
-    };
+#define RPO_LOAD_SLAB(k0)                                                                            \
+    {                                                                                                \
+        const bool k_ok = (k0) + ld_k < k_end;                                                       \
+        _Pragma("unroll") for (int i = 0; i < A_CHUNKS; ++i) {                                       \
+            const bool ok = k_ok && (m0 + ld_row + i * ROWS_PER_PASS) < M;                           \
+            ra[i] = ok ? *(const u32x4_t*)(a_base + (int64_t)i * ROWS_PER_PASS * lda + (k0)) : zero4;  \
+        }                                                                                            \
+        _Pragma("unroll") for (int i = 0; i < B_CHUNKS; ++i) {                                       \
+            const bool ok = k_ok && b_off[i] >= 0;                                                   \
+            rb[i] = ok ? *(const u32x4_t*)(W + b_off[i] + (k0)) : zero4;                               \
+        }                                                                                            \
+    }
+#define RPO_STORE_SLAB(buf)                                                                          \
+    {                                                                                                \
+        bf16* as_ = As + (buf) * BM * kLdsRow + ld_row * kLdsRow + ld_k;                             \
+        bf16* bs_ = Bs + (buf) * BN * kLdsRow + ld_row * kLdsRow + ld_k;                             \
+        _Pragma("unroll") for (int i = 0; i < A_CHUNKS; ++i)                                         \
+            *(u32x4_t*)(as_ + i * ROWS_PER_PASS * kLdsRow) = ra[i];                                    \
+        _Pragma("unroll") for (int i = 0; i < B_CHUNKS; ++i)                                         \
+            *(u32x4_t*)(bs_ + i * ROWS_PER_PASS * kLdsRow) = rb[i];                                    \
+    }
+    const u32x4_t zero4 = {0u, 0u, 0u, 0u};
 
     f32x16_t acc[MI][NI];
 #pragma unroll
@@ -149,14 +199,16 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_kernel(const bf16* __re
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-    const int nk = (K + kBK - 1) / kBK;
-    load_slab(0);
-    store_slab(0);
+    const int nk = (k_end - k_begin + kBK - 1) / kBK;
+    if (nk > 0) {
+        RPO_LOAD_SLAB(k_begin);
+        RPO_STORE_SLAB(0);
+    }
     __syncthreads();
     const int frag_row = lane & 31, frag_k = (lane >> 5) * 8;
     for (int kt = 0; kt < nk; ++kt) {
         const int buf = kt & 1;
-        if (kt + 1 < nk) load_slab((kt + 1) * kBK);
+        if (kt + 1 < nk) RPO_LOAD_SLAB(k_begin + (kt + 1) * kBK);
         const bf16* as = As + buf * BM * kLdsRow + (wm * TM + frag_row) * kLdsRow + frag_k;
         const bf16* bs = Bs + buf * BN * kLdsRow + (wn * TN + frag_row) * kLdsRow + frag_k;
 #pragma unroll
@@ -172,11 +224,34 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_kernel(const bf16* __re
                 for (int j = 0; j < NI; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
         }
-        if (kt + 1 < nk) store_slab(buf ^ 1);
+        if (kt + 1 < nk) RPO_STORE_SLAB(buf ^ 1);
         __syncthreads();
     }
 
+#undef RPO_LOAD_SLAB
+#undef RPO_STORE_SLAB
+
     const int col_in = lane & 31, row_in = (lane >> 5) * 4;
+    if (EPI == kEpiSwiglu) {
+        // blocks (j, j + 1) = (gate, up) of output columns (n0 + wn*TN)/2 + (j/2)*32 + col_in
+        bf16* C = (bf16*)Cv;
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; j += 2) {
+                const int vn = n0 + wn * TN + j * 32;  // virtual column of the gate block
+                if (vn + col_in >= N) continue;         // N = 2F is a multiple of 64: pairs are whole
+                const int oc = (vn >> 1) + col_in;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int gm = m0 + wm * TM + i * 32 + 8 * (e >> 2) + row_in + (e & 3);
+                    if (gm >= M) continue;
+                    C[(int64_t)gm * ldc + oc] = f32_to_bf16(silu_f(acc[i][j][e]) * acc[i][j + 1][e]);
+                }
+            }
+        return;
+    }
+    float* Cp = (float*)Cv + (EPI == kEpiPartial ? (int64_t)blockIdx.y * M * (int64_t)N : 0);
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
 #pragma unroll
@@ -187,47 +262,161 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_kernel(const bf16* __re
             for (int e = 0; e < 16; ++e) {
                 const int gm = m0 + wm * TM + i * 32 + 8 * (e >> 2) + row_in + (e & 3);
                 if (gm >= M) continue;
-                const int64_t o = (int64_t)gm * ldc + gn;
                 const float v = acc[i][j][e];
                 if (EPI == kEpiStore)
-                    ((bf16*)Cv)[o] = f32_to_bf16(v);
+                    ((bf16*)Cv)[(int64_t)gm * ldc + gn] = f32_to_bf16(v);
                 else if (EPI == kEpiStoreF32)
-                    ((float*)Cv)[o] = v;
+                    ((float*)Cv)[(int64_t)gm * ldc + gn] = v;
+                else if (EPI == kEpiAddF32)
+                    ((float*)Cv)[(int64_t)gm * ldc + gn] += v;
                 else
-                    ((float*)Cv)[o] += v;
+                    Cp[(int64_t)gm * N + gn] = v;
             }
         }
     }
 }
 
-template <int BM, int BN, int WM, int WN>
-static hipError_t launch_mfma_cfg(const GemmArgs& a, hipStream_t s) {
+// Sum the K-split partials [splits][M][N] and apply the epilogue.  One thread per output
+// element (per gate/up pair in SwiGLU mode); partial sums are added in split order.
+template <int EPI>
+__global__ __launch_bounds__(256) void gemm_splitk_reduce_kernel(const float* __restrict__ P, int splits,
+                                                                 int M, int N, void* __restrict__ Cv,
+                                                                 int64_t ldc) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t plane = (int64_t)M * N;
+    if (EPI == kEpiSwiglu) {
+        const int F = N / 2;
+        if (idx >= (int64_t)M * F) return;
+        const int m = (int)(idx / F), oc = (int)(idx % F);
+        const int vg = ((oc >> 5) << 6) + (oc & 31);  // virtual gate column; up is 32 further
+        float g = 0.f, u = 0.f;
+        for (int z = 0; z < splits; ++z) {
+            g += P[z * plane + (int64_t)m * N + vg];
+            u += P[z * plane + (int64_t)m * N + vg + 32];
+        }
+        ((bf16*)Cv)[(int64_t)m * ldc + oc] = f32_to_bf16(silu_f(g) * u);
+        return;
+    }
+    if (idx >= plane) return;
+    const int m = (int)(idx / N), n = (int)(idx % N);
+    float v = 0.f;
+    for (int z = 0; z < splits; ++z) v += P[z * plane + idx];
+    const int64_t o = (int64_t)m * ldc + n;
+    if (EPI == kEpiStore)
+        ((bf16*)Cv)[o] = f32_to_bf16(v);
+    else if (EPI == kEpiStoreF32)
+        ((float*)Cv)[o] = v;
+    else
+        ((float*)Cv)[o] += v;
+}
+
+// ---------------------------------------------------------------------------
+// launch logic
+// ---------------------------------------------------------------------------
+namespace {
+
+struct TileCfg {
+    int id;  // KernelId base (store variant)
+    int bm, bn;
+};
+
+bool mfma_ok(const GemmArgs& a) {
+    // 16-byte operand loads: K-contiguous rows whose starts and strides are multiples of 8 elements.
+    const bool vec_ok = (a.K % 8 == 0) && (a.lda % 8 == 0) && (a.ldw % 8 == 0) &&
+                        ((uintptr_t)a.A % 16 == 0) && ((uintptr_t)a.W % 16 == 0);
+    if (a.dtype != kBF16 || a.path == 1 || !vec_ok) return false;
+    if (a.epilogue == kEpiSwiglu && (a.N % 64 != 0)) return false;  // N = 2F, F a multiple of 32
+    return true;
+}
+
+TileCfg pick_tile(const GemmArgs& a) {
+    if (a.M > 512) return TileCfg{kKidGemm256, 256, 256};
+    if (a.M > 128) return TileCfg{kKidGemm256x128, 256, 128};
+    if (a.M > 64) return TileCfg{kKidGemm128, 128, 128};
+    return TileCfg{kKidGemm64, 64, 128};
+}
+
+// How many K splits: fill the chip (>= ~256 workgroups) without making the slabs per split
+// too few, and only when the workspace can hold the partials.
+int pick_splits(const GemmArgs& a, const TileCfg& t) {
+    const int tiles = ceil_div(a.M, t.bm) * ceil_div(a.N, t.bn);
+    if (tiles >= 192 || a.K < 1024) return 1;
+    int splits = ceil_div(256, tiles);
+    const int max_by_k = a.K / 512;  // at least 8 slabs per split
+    splits = splits < max_by_k ? splits : max_by_k;
+    if (splits > 16) splits = 16;
+    while (splits > 1 && (size_t)splits * a.M * a.N * 4 > a.ws_bytes) --splits;
+    return splits < 1 ? 1 : splits;
+}
+
+template <int BM, int BN, int WM, int WN, int EPI, bool SWIGLU>
+hipError_t launch_one(const GemmArgs& a, int splits, void* out, hipStream_t s) {
     const int gm = ceil_div(a.M, BM), gn = ceil_div(a.N, BN);
+    const int n_tiles = gm * gn;
+    const int per_xcd = ceil_div(n_tiles, kXcd);
     const size_t lds = (size_t)2 * (BM + BN) * kLdsRow * sizeof(bf16);
-    const dim3 grid((unsigned)(gm * gn)), block(WM * WN * 64);
-#define RPO_GEMM_CASE(E)                                                                              \
-    case E: {                                                                                         \
-        auto kern = gemm_mfma_kernel<BM, BN, WM, WN, E>;                                              \
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, \
-                                           (int)lds);                                                 \
-        if (e != hipSuccess) return e;                                                                \
-        kern<<<grid, block, lds, s>>>((const bf16*)a.A, a.lda, (const bf16*)a.W, a.ldw, a.C, a.ldc,   \
-                                      a.M, a.N, a.K, gm);                                             \
-        break;                                                                                        \
+    auto kern = gemm_mfma_kernel<BM, BN, WM, WN, EPI, SWIGLU>;
+    static bool attr_set = false;  // one flag per template instance
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
     }
-    switch (a.epilogue) {
-        RPO_GEMM_CASE(kEpiStore)
-        RPO_GEMM_CASE(kEpiStoreF32)
-        RPO_GEMM_CASE(kEpiAddF32)
-        default:
-            return hipErrorInvalidValue;
-    }
-#undef RPO_GEMM_CASE
+    int k_per_split = ceil_div(ceil_div(a.K, splits), kBK) * kBK;
+    const dim3 grid((unsigned)(per_xcd * kXcd), (unsigned)splits), block(WM * WN * 64);
+    kern<<<grid, block, lds, s>>>((const bf16*)a.A, a.lda, (const bf16*)a.W, a.ldw, out, a.ldc, a.M, a.N, a.K,
+                                  gm, n_tiles, k_per_split, a.N / 2);
     return hipGetLastError();
 }
 
+template <int BM, int BN, int WM, int WN>
+hipError_t launch_tile(const GemmArgs& a, int splits, hipStream_t s) {
+    const bool sw = a.epilogue == kEpiSwiglu;
+    if (splits > 1) {
+        hipError_t e = sw ? launch_one<BM, BN, WM, WN, kEpiPartial, true>(a, splits, a.ws, s)
+                          : launch_one<BM, BN, WM, WN, kEpiPartial, false>(a, splits, a.ws, s);
+        if (e != hipSuccess) return e;
+        const int64_t n_out = sw ? (int64_t)a.M * (a.N / 2) : (int64_t)a.M * a.N;
+        const unsigned blocks = (unsigned)ceil_div64(n_out, 256);
+        const float* P = (const float*)a.ws;
+        switch (a.epilogue) {
+            case kEpiStore:
+                gemm_splitk_reduce_kernel<kEpiStore><<<blocks, 256, 0, s>>>(P, splits, a.M, a.N, a.C, a.ldc);
+                break;
+            case kEpiStoreF32:
+                gemm_splitk_reduce_kernel<kEpiStoreF32><<<blocks, 256, 0, s>>>(P, splits, a.M, a.N, a.C, a.ldc);
+                break;
+            case kEpiAddF32:
+                gemm_splitk_reduce_kernel<kEpiAddF32><<<blocks, 256, 0, s>>>(P, splits, a.M, a.N, a.C, a.ldc);
+                break;
+            default:
+                gemm_splitk_reduce_kernel<kEpiSwiglu><<<blocks, 256, 0, s>>>(P, splits, a.M, a.N, a.C, a.ldc);
+                break;
+        }
+        return hipGetLastError();
+    }
+    switch (a.epilogue) {
+        case kEpiStore:
+            return launch_one<BM, BN, WM, WN, kEpiStore, false>(a, 1, a.C, s);
+        case kEpiStoreF32:
+            return launch_one<BM, BN, WM, WN, kEpiStoreF32, false>(a, 1, a.C, s);
+        case kEpiAddF32:
+            return launch_one<BM, BN, WM, WN, kEpiAddF32, false>(a, 1, a.C, s);
+        case kEpiSwiglu:
+            return launch_one<BM, BN, WM, WN, kEpiSwiglu, true>(a, 1, a.C, s);
+        default:
+            return hipErrorInvalidValue;
+    }
+}
+
 template <typename T>
-static hipError_t launch_generic(const GemmArgs& a, hipStream_t s) {
+hipError_t launch_generic(const GemmArgs& a, hipStream_t s) {
+    if (a.epilogue == kEpiSwiglu) {
+        const int F = a.N / 2;
+        gemm_generic_swiglu_kernel<T><<<dim3(ceil_div(F, 256), a.M), 256, 0, s>>>(
+            (const T*)a.A, a.lda, (const T*)a.W, a.ldw, (T*)a.C, a.ldc, a.M, F, a.K);
+        return hipGetLastError();
+    }
     const dim3 grid(ceil_div(a.N, 64), ceil_div(a.M, 64));
     switch (a.epilogue) {
         case kEpiStore:
@@ -248,15 +437,28 @@ static hipError_t launch_generic(const GemmArgs& a, hipStream_t s) {
     return hipGetLastError();
 }
 
+}  // namespace
+
+int gemm_kernel_id(const GemmArgs& a) {
+    if (!mfma_ok(a)) return kKidGemmGeneric;
+    return pick_tile(a).id;
+}
+
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
     if (a.M <= 0 || a.N <= 0) return hipSuccess;
-    if (a.dtype == kF32) return launch_generic<float>(a, s);
-    // 16-byte operand loads: K-contiguous rows whose starts and strides are multiples of 8 elements.
-    const bool vec_ok = (a.K % 8 == 0) && (a.lda % 8 == 0) && (a.ldw % 8 == 0) &&
-                        ((uintptr_t)a.A % 16 == 0) && ((uintptr_t)a.W % 16 == 0);
-    if (a.path == 1 || !vec_ok) return launch_generic<bf16>(a, s);
-    if (a.M <= 64) return launch_mfma_cfg<64, 128, 1, 4>(a, s);
-    return launch_mfma_cfg<128, 128, 2, 2>(a, s);
+    if (!mfma_ok(a)) return a.dtype == kF32 ? launch_generic<float>(a, s) : launch_generic<bf16>(a, s);
+    const TileCfg t = pick_tile(a);
+    const int splits = (a.ws && a.ws_bytes) ? pick_splits(a, t) : 1;
+    switch (t.id) {
+        case kKidGemm256:
+            return launch_tile<256, 256, 2, 2>(a, splits, s);
+        case kKidGemm256x128:
+            return launch_tile<256, 128, 2, 2>(a, splits, s);
+        case kKidGemm128:
+            return launch_tile<128, 128, 2, 2>(a, splits, s);
+        default:
+            return launch_tile<64, 128, 1, 2>(a, splits, s);
+    }
 }
 
 }  // namespace rpo

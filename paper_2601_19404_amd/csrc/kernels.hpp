@@ -23,6 +23,8 @@ enum Epilogue : int {
     kEpiStore = 0,     // C has the input dtype
     kEpiStoreF32 = 1,  // C is fp32
     kEpiAddF32 = 2,    // C is fp32 and is accumulated into (residual stream)
+    kEpiSwiglu = 3,    // W = [gate rows; up rows] (N = 2F): C[M, F] = silu(A Wg^T) * (A Wu^T), input dtype
+    kEpiPartial = 4,   // internal: fp32 partial sums of one K split
 };
 struct GemmArgs {
     const void* A;
@@ -35,8 +37,26 @@ struct GemmArgs {
     int dtype;     // element type of A and W
     int epilogue;  // Epilogue
     int path;      // 0 = pick, 1 = force the generic (non-MFMA) kernel
+    void* ws;      // fp32 scratch for K-split partial sums (may be null: no splitting)
+    size_t ws_bytes;
 };
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
+
+// Identifiers of the kernels whose launches can be timed (rpo_profile_start).
+enum KernelId : int {
+    kKidNone = 0,
+    kKidGemm256 = 1,        // gemm_mfma_kernel<256,256,2,2,*> (M > 512)
+    kKidGemm256x128 = 2,    // gemm_mfma_kernel<256,128,2,2,*> (128 < M <= 512)
+    kKidGemm128 = 3,        // gemm_mfma_kernel<128,128,2,2,*> (64 < M <= 128)
+    kKidGemm64 = 4,         // gemm_mfma_kernel<64,128,1,2,*>  (M <= 64)
+    kKidGemmGeneric = 7,
+    kKidAttnDecode = 8,     // attn_decode_mfma_kernel
+    kKidAttnChunk = 9,      // attn_chunk_mfma_kernel
+    kKidSample = 10,        // sample_kernel
+    kKidCount = 11,
+};
+// Which kernel launch_gemm picks for these arguments.
+int gemm_kernel_id(const GemmArgs& a);
 
 // ---- elementwise ---------------------------------------------------------------
 // x[r, :] = embed[tokens[idx(r)], :] as fp32, idx(r) = tok_index ? tok_index[r] : r;
@@ -100,6 +120,8 @@ struct AttnArgs {
     int path;  // 0 = pick, 1 = force generic
 };
 hipError_t launch_attn_chunk(const AttnArgs& a, hipStream_t s);
+// Whether the MFMA attention kernels take these arguments.
+bool attn_uses_mfma(const AttnArgs& a);
 
 // Decode attention with a shared prefix: rollout rows r = g * G + i, one new query row
 // each; rows of a group share the group's first shared_pages[g] pages.

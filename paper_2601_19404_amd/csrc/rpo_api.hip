@@ -46,6 +46,74 @@ extern "C" int rpo_set_kernel_path(int path) {
 }
 
 // ---------------------------------------------------------------------------
+// per-kernel timing: HIP event pairs around every launch of one chosen kernel
+// ---------------------------------------------------------------------------
+namespace {
+struct Profile {
+    int kernel_id = 0;
+    std::vector<hipEvent_t> events;  // pool, reused across sessions
+    size_t used = 0;
+    double flops = 0.0, bytes = 0.0;
+    hipError_t mark(hipStream_t s) {
+        if (used == events.size()) {
+            hipEvent_t e;
+            hipError_t r = hipEventCreate(&e);
+            if (r != hipSuccess) return r;
+            events.push_back(e);
+        }
+        return hipEventRecord(events[used++], s);
+    }
+};
+Profile g_prof;
+
+// Runs `launch` and, when kernel `id` is the one being timed, brackets it with events.
+template <typename F>
+hipError_t timed(int id, double flops, double bytes, hipStream_t s, F&& launch) {
+    const bool on = id != 0 && id == g_prof.kernel_id;
+    if (on) {
+        hipError_t e = g_prof.mark(s);
+        if (e != hipSuccess) return e;
+    }
+    hipError_t e = launch();
+    if (e != hipSuccess) return e;
+    if (on) {
+        e = g_prof.mark(s);
+        g_prof.flops += flops;
+        g_prof.bytes += bytes;
+    }
+    return e;
+}
+}  // namespace
+
+extern "C" int rpo_profile_start(int kernel_id) {
+    if (kernel_id <= 0 || kernel_id >= kKidCount) return fail(RPO_EINVAL, "rpo_profile_start: unknown kernel id");
+    g_prof.kernel_id = kernel_id;
+    g_prof.used = 0;
+    g_prof.flops = g_prof.bytes = 0.0;
+    return RPO_OK;
+}
+
+extern "C" int rpo_profile_stop(int64_t* n_launches, double* total_ms, double* total_flops, double* total_bytes) {
+    if (!n_launches || !total_ms || !total_flops || !total_bytes)
+        return fail(RPO_EINVAL, "rpo_profile_stop: NULL argument");
+    double ms = 0.0;
+    const size_t n = g_prof.used / 2;
+    if (n) HIP_TRY(hipEventSynchronize(g_prof.events[g_prof.used - 1]));
+    for (size_t i = 0; i < n; ++i) {
+        float t = 0.f;
+        HIP_TRY(hipEventElapsedTime(&t, g_prof.events[2 * i], g_prof.events[2 * i + 1]));
+        ms += t;
+    }
+    *n_launches = (int64_t)n;
+    *total_ms = ms;
+    *total_flops = g_prof.flops;
+    *total_bytes = g_prof.bytes;
+    g_prof.kernel_id = 0;
+    g_prof.used = 0;
+    return RPO_OK;
+}
+
+// ---------------------------------------------------------------------------
 // handles
 // ---------------------------------------------------------------------------
 struct rpo_model {
@@ -58,6 +126,7 @@ struct rpo_model {
 namespace {
 
 constexpr size_t kAlign = 256;
+constexpr size_t kSplitKBytes = (size_t)96 << 20;
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct BatchDims {
@@ -113,7 +182,7 @@ WsLayout make_layout(const rpo_model* m, const BatchDims& bd) {
     L.h = take(R * d.d_model * es);
     L.qkv = take(R * m->qkv_width() * es);
     L.attn = take(R * (size_t)d.n_q_heads * d.head_dim * es);
-    L.gu = take(R * 2 * (size_t)d.d_ffn * es);
+    L.gu = take(kSplitKBytes);  // fp32 partial sums of K-split GEMMs
     L.act = take(R * (size_t)d.d_ffn * es);
     L.hl = take((size_t)bd.lm_rows * d.d_model * es);
     L.logits = take((size_t)std::min(bd.max_rows, 1024) * d.vocab * 4);
@@ -300,6 +369,8 @@ struct PassCfg {
     const uint8_t* active;
     bool decode;             // one row per rollout against the shared-prefix cache
     int max_shared_pages;
+    double attn_flops = 0.0;  // algorithmic work of ONE layer's attention launch (for timing reports)
+    double attn_bytes = 0.0;
 };
 
 #define RET_IF(expr)                       \
@@ -308,8 +379,9 @@ struct PassCfg {
         if (e__ != hipSuccess) return e__; \
     } while (0)
 
-hipError_t gemm(const rpo_model* m, const void* A, int64_t lda, const void* W, int64_t ldw, void* C,
+hipError_t gemm(rpo_batch* b, const void* A, int64_t lda, const void* W, int64_t ldw, void* C,
                 int64_t ldc, int M, int N, int K, int epi, hipStream_t s) {
+    const rpo_model* m = b->m;
     GemmArgs g;
     g.A = A;
     g.lda = lda;
@@ -323,7 +395,15 @@ hipError_t gemm(const rpo_model* m, const void* A, int64_t lda, const void* W, i
     g.dtype = m->d.dtype;
     g.epilogue = epi;
     g.path = g_kernel_path;
-    return launch_gemm(g, s);
+    g.ws = b->at<void>(b->L.gu);
+    g.ws_bytes = kSplitKBytes;
+    const double es = (double)dtype_size(g.dtype);
+    const double out_bytes = epi == kEpiStore ? (double)M * N * es
+                             : epi == kEpiStoreF32 ? (double)M * N * 4.0
+                             : epi == kEpiAddF32 ? (double)M * N * 8.0
+                                                 : (double)M * (N / 2) * es;
+    return timed(gemm_kernel_id(g), 2.0 * M * N * K, ((double)M * K + (double)N * K) * es + out_bytes, s,
+                 [&] { return launch_gemm(g, s); });
 }
 
 hipError_t run_layers(rpo_batch* b, const PassCfg& pc, hipStream_t s) {
@@ -334,13 +414,12 @@ hipError_t run_layers(rpo_batch* b, const PassCfg& pc, hipStream_t s) {
     void* h = b->at<void>(L.h);
     void* qkv = b->at<void>(L.qkv);
     void* attn = b->at<void>(L.attn);
-    void* gu = b->at<void>(L.gu);
     void* act = b->at<void>(L.act);
     const int qw = m->qkv_width();
     const int qd = d.n_q_heads * d.head_dim;
     for (int l = 0; l < d.n_layers; ++l) {
         RET_IF(launch_rmsnorm(x, nullptr, m->attn_norm[l], d.dtype, d.d_model, d.rms_eps, h, pc.rows, s));
-        RET_IF(gemm(m, h, d.d_model, m->wqkv[l], d.d_model, qkv, qw, pc.rows, qw, d.d_model, kEpiStore, s));
+        RET_IF(gemm(b, h, d.d_model, m->wqkv[l], d.d_model, qkv, qw, pc.rows, qw, d.d_model, kEpiStore, s));
         RopeKvArgs ra;
         ra.qkv = qkv;
         ra.dtype = d.dtype;
@@ -388,16 +467,17 @@ hipError_t run_layers(rpo_batch* b, const PassCfg& pc, hipStream_t s) {
             da.max_own_pages = b->bd.ppr;
             da.partial = b->at<float>(L.partial);
             da.partial_floats = attn_decode_partial_floats(b->bd.B, d.n_q_heads, d.head_dim, b->bd.ppg);
-            RET_IF(launch_attn_decode(da, s));
+            RET_IF(timed(attn_uses_mfma(aa) ? kKidAttnDecode : 0, pc.attn_flops, pc.attn_bytes, s,
+                         [&] { return launch_attn_decode(da, s); }));
         } else {
-            RET_IF(launch_attn_chunk(aa, s));
+            RET_IF(timed(attn_uses_mfma(aa) ? kKidAttnChunk : 0, pc.attn_flops, pc.attn_bytes, s,
+                         [&] { return launch_attn_chunk(aa, s); }));
         }
-        RET_IF(gemm(m, attn, qd, m->wo[l], qd, x, d.d_model, pc.rows, d.d_model, qd, kEpiAddF32, s));
+        RET_IF(gemm(b, attn, qd, m->wo[l], qd, x, d.d_model, pc.rows, d.d_model, qd, kEpiAddF32, s));
         RET_IF(launch_rmsnorm(x, nullptr, m->ffn_norm[l], d.dtype, d.d_model, d.rms_eps, h, pc.rows, s));
-        RET_IF(gemm(m, h, d.d_model, m->w_gate_up[l], d.d_model, gu, 2 * d.d_ffn, pc.rows, 2 * d.d_ffn,
-                    d.d_model, kEpiStore, s));
-        RET_IF(launch_swiglu(gu, d.dtype, d.d_ffn, act, pc.rows, s));
-        RET_IF(gemm(m, act, d.d_ffn, m->w_down[l], d.d_ffn, x, d.d_model, pc.rows, d.d_model, d.d_ffn,
+        RET_IF(gemm(b, h, d.d_model, m->w_gate_up[l], d.d_model, act, d.d_ffn, pc.rows, 2 * d.d_ffn, d.d_model,
+                    kEpiSwiglu, s));
+        RET_IF(gemm(b, act, d.d_ffn, m->w_down[l], d.d_ffn, x, d.d_model, pc.rows, d.d_model, d.d_ffn,
                     kEpiAddF32, s));
     }
     return hipSuccess;
@@ -410,7 +490,7 @@ hipError_t lm_head_rows(rpo_batch* b, const int32_t* row_idx, int n, float* logi
     void* hl = b->at<void>(b->L.hl);
     RET_IF(launch_rmsnorm(b->at<float>(b->L.x), row_idx, m->final_norm, d.dtype, d.d_model, d.rms_eps, hl, n,
                           s));
-    return gemm(m, hl, d.d_model, m->lm_head, d.d_model, logits, d.vocab, n, d.vocab, d.d_model,
+    return gemm(b, hl, d.d_model, m->lm_head, d.d_model, logits, d.vocab, n, d.vocab, d.d_model,
                 kEpiStoreF32, s);
 }
 
@@ -554,6 +634,22 @@ extern "C" int rpo_decode_step(rpo_batch* b, const int32_t* tokens_dev, int32_t 
     pc.active = active_dev;
     pc.decode = true;
     pc.max_shared_pages = max_shared;
+    {
+        // Algorithmic work of one layer's decode attention: the shared prefix pages of every live
+        // group are read ONCE per group, each rollout's private tokens once per rollout.
+        const double tok_bytes = 2.0 * d.n_kv_heads * d.head_dim * dtype_size(d.dtype);
+        double toks = 0.0, qk = 0.0;
+        for (int r = 0; r < n_rows; ++r) {
+            const int g = r / bd.G;
+            const int ctx = b->prefix_len[g] + b->step + 1;
+            const int shared_tok = (b->prefix_len[g] / bd.pt) * bd.pt;
+            toks += ctx - shared_tok;
+            if (r % bd.G == 0) toks += shared_tok;
+            qk += ctx;
+        }
+        pc.attn_bytes = toks * tok_bytes;
+        pc.attn_flops = 4.0 * qk * d.n_q_heads * d.head_dim;
+    }
     HIP_TRY(run_layers(b, pc, s));
     HIP_TRY(lm_head_rows(b, nullptr, n_rows, logits_dev, s));
     b->step += 1;
@@ -671,7 +767,8 @@ extern "C" int rpo_sample(const float* logits_dev, int32_t n_logit_rows, int32_t
     a.step = step;
     a.tokens_out = tokens_out_dev;
     a.logprob_out = logprob_out_dev;
-    HIP_TRY(launch_sample(a, (hipStream_t)stream));
+    HIP_TRY(timed(kKidSample, 0.0, (double)n_out_rows * vocab * 4.0, (hipStream_t)stream,
+                  [&] { return launch_sample(a, (hipStream_t)stream); }));
     return RPO_OK;
 }
 
@@ -688,11 +785,14 @@ extern "C" int grpo_advantages(const float* rewards_dev, int32_t n_groups, int32
 // ---------------------------------------------------------------------------
 extern "C" int rpo_gemm_nt(const void* a_dev, int64_t lda, const void* w_dev, int64_t ldw, void* c_dev,
                            int64_t ldc, int32_t M, int32_t N, int32_t K, int32_t dtype, int32_t epilogue,
-                           void* stream) {
+                           void* ws_dev, size_t ws_bytes, void* stream) {
     if (!a_dev || !w_dev || !c_dev) return fail(RPO_EINVAL, "rpo_gemm_nt: NULL argument");
-    if (M < 0 || N < 0 || K < 1 || lda < K || ldw < K || ldc < N) return fail(RPO_EINVAL, "rpo_gemm_nt: bad sizes");
+    if (M < 0 || N < 0 || K < 1 || lda < K || ldw < K || ldc < (epilogue == 3 ? N / 2 : N))
+        return fail(RPO_EINVAL, "rpo_gemm_nt: bad sizes");
     if (dtype != RPO_F32 && dtype != RPO_BF16) return fail(RPO_EINVAL, "rpo_gemm_nt: unknown dtype");
-    if (epilogue < 0 || epilogue > 2) return fail(RPO_EINVAL, "rpo_gemm_nt: unknown epilogue");
+    if (epilogue < 0 || epilogue > 3) return fail(RPO_EINVAL, "rpo_gemm_nt: unknown epilogue");
+    if (epilogue == 3 && (N % 2)) return fail(RPO_EINVAL, "rpo_gemm_nt: SwiGLU needs N = 2F");
+    if ((ws_dev == nullptr) != (ws_bytes == 0)) return fail(RPO_EINVAL, "rpo_gemm_nt: ws_dev / ws_bytes mismatch");
     GemmArgs g;
     g.A = a_dev;
     g.lda = lda;
@@ -706,6 +806,8 @@ extern "C" int rpo_gemm_nt(const void* a_dev, int64_t lda, const void* w_dev, in
     g.dtype = dtype;
     g.epilogue = epilogue;
     g.path = g_kernel_path;
+    g.ws = ws_dev;
+    g.ws_bytes = ws_bytes;
     HIP_TRY(launch_gemm(g, (hipStream_t)stream));
     return RPO_OK;
 }

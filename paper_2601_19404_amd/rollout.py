@@ -88,10 +88,19 @@ def suffix_rollout(batch: rpo.Batch, prompts, cached, m, temperature: float, see
                          int(m.sum()) * G, kept)
 
 
-def pack_suffixes(tokens: torch.Tensor, m, G: int):
-    """tokens [B, max_m] + per-group m -> (packed int32 device tensor, cu_suffix[B+1])."""
+def suffix_index(m, G: int, max_m: int):
+    """Flat positions, inside a [B, max_m] token matrix, of every rollout's m tokens in row
+    order, and the cumulative suffix lengths cu_suffix[B+1] (host integers only)."""
     lens = np.repeat(np.asarray(m, np.int64), G)
     cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
-    B, max_m = tokens.shape
-    mask = torch.arange(max_m, device=tokens.device)[None, :] < torch.from_numpy(lens).to(tokens.device)[:, None]
-    return tokens[mask].contiguous(), cu
+    rows = np.repeat(np.arange(len(lens), dtype=np.int64), lens)
+    cols = np.arange(int(cu[-1]), dtype=np.int64) - np.repeat(cu[:-1].astype(np.int64), lens)
+    return rows * max_m + cols, cu
+
+
+def pack_suffixes(tokens: torch.Tensor, m, G: int, index_dev: torch.Tensor | None = None):
+    """tokens [B, max_m] + per-group m -> (packed int32 device tensor, cu_suffix[B+1])."""
+    idx, cu = suffix_index(m, G, tokens.shape[1])
+    if index_dev is None:
+        index_dev = torch.from_numpy(idx).to(tokens.device)
+    return tokens.reshape(-1)[index_dev].contiguous(), cu

@@ -19,7 +19,7 @@ def rpo():
     binding.rpo_set_kernel_path(0)
 
 
-def _gemm_case(rpo, M, N, K, dtype, epi, path, seed=0, pad=0):
+def _gemm_case(rpo, M, N, K, dtype, epi, path, seed=0, pad=0, ws_mb=0):
     g = torch.Generator().manual_seed(seed)
     a = torch.randn(M, K + pad, generator=g).to(dtype)[:, :K]
     w = (torch.randn(N, K + pad, generator=g) * 0.1).to(dtype)[:, :K]
@@ -33,8 +33,9 @@ def _gemm_case(rpo, M, N, K, dtype, epi, path, seed=0, pad=0):
         cd = torch.zeros(M, N + pad, dtype=dtype, device="cuda")[:, :N]
     else:
         cd = torch.empty(M, N + pad, dtype=torch.float32, device="cuda")[:, :N].copy_(c0[:, :N])
+    ws = torch.empty(ws_mb << 20, dtype=torch.uint8, device="cuda") if ws_mb else None
     rpo.rpo_set_kernel_path(path)
-    rpo.rpo_gemm_nt(ad, wd, cd, epi)
+    rpo.rpo_gemm_nt(ad, wd, cd, epi, ws)
     torch.cuda.synchronize()
     got = cd.float().cpu().numpy().astype(np.float64)
     if epi == 2:
@@ -54,9 +55,33 @@ def test_gemm_mfma_bf16(rpo, shape, epi):
     _gemm_case(rpo, *shape, torch.bfloat16, epi, path=0)
 
 
-@pytest.mark.parametrize("shape", [(512, 2048, 1536), (64, 4096, 1536), (200, 1536, 8960)])
-def test_gemm_mfma_bf16_model_shapes(rpo, shape):
-    _gemm_case(rpo, *shape, torch.bfloat16, 1, path=0, seed=3)
+@pytest.mark.parametrize("ws_mb", [0, 64])
+@pytest.mark.parametrize("shape", [(512, 2048, 1536), (64, 4096, 1536), (200, 1536, 8960), (1000, 640, 1536),
+                                   (504, 1536, 8960), (8, 1536, 8960)])
+def test_gemm_mfma_bf16_model_shapes(rpo, shape, ws_mb):
+    """Every tile shape (256x256, 256x128, 128x128, 64x128), with and without K splitting."""
+    for epi in (0, 1, 2):
+        _gemm_case(rpo, *shape, torch.bfloat16, epi, path=0, seed=3, ws_mb=ws_mb)
+
+
+@pytest.mark.parametrize("path,ws_mb", [(0, 0), (0, 64), (1, 0)])
+@pytest.mark.parametrize("M,F,K", [(512, 8960, 1536), (40, 1024, 768), (700, 256, 2048), (130, 96, 1024)])
+def test_gemm_swiglu(rpo, M, F, K, path, ws_mb):
+    """Fused gate/up projection: C = silu(A Wg^T) * (A Wu^T), W = [gate rows; up rows]."""
+    g = torch.Generator().manual_seed(M + F)
+    a = torch.randn(M, K, generator=g).to(torch.bfloat16)
+    w = (torch.randn(2 * F, K, generator=g) * 0.05).to(torch.bfloat16)
+    gu = T.lm_head({"lm_head": w.float().numpy()}, a.float().numpy())
+    ref = T.silu(gu[:, :F]) * gu[:, F:]
+    c = torch.zeros(M, F, dtype=torch.bfloat16, device="cuda")
+    ws = torch.empty(ws_mb << 20, dtype=torch.uint8, device="cuda") if ws_mb else None
+    rpo.rpo_set_kernel_path(path)
+    rpo.rpo_gemm_nt(a.cuda(), w.cuda(), c, 3, ws)
+    torch.cuda.synchronize()
+    got = c.float().cpu().numpy().astype(np.float64)
+    err = np.abs(got - ref)
+    tol = 2.0 ** -8 * np.abs(ref) + 3e-5 * np.sqrt(K)
+    assert np.all(err <= tol), f"max err {err.max()}"
 
 
 def test_gemm_mfma_bf16_padded_strides(rpo):

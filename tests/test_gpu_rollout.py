@@ -82,6 +82,8 @@ def run_case(rpo, mcfg, prompts, cached, m, G, temperature=1.0, seed=3, page=64,
             for j in range(mg):
                 got = kept[j][g if j == 0 else r]
                 worst = max(worst, float(np.max(np.abs(got - ref[j]))))
+                sq += float(np.sum((got - ref[j]) ** 2))
+                cnt += got.size
             lp_ref = T.log_softmax(ref / temperature)[np.arange(mg), toks[r, :mg]]
             assert np.max(np.abs(slp[r, :mg] - lp_ref)) < tol, "sampler log-prob"
     print(f"[{mcfg.name} path={path}] logits vs oracle: max {worst:.3e} rms {np.sqrt(sq / max(cnt, 1)):.3e} "
