@@ -110,7 +110,7 @@ def main():
     ap.add_argument("--workload", default="C1", choices=["C0", "C1", "C2", "C3"])
     ap.add_argument("--groups", type=int, default=None, help="override the number of groups (debugging)")
     ap.add_argument("--max-rows", type=int, default=16384)
-    ap.add_argument("--profile-kernel", default="gemm256x128",
+    ap.add_argument("--profile-kernel", default="gemm256",
                     help="kernel whose launches are timed with HIP events for the roofline object")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()

@@ -33,8 +33,10 @@ int rpo_gemm_nt(const void *a_dev, int64_t lda, const void *w_dev, int64_t ldw, 
                 size_t ws_bytes, void *stream);
 
 /* Process-wide kernel selection: 0 = fastest available kernel for the shape (default),
- * 1 = generic vector-ALU kernels for GEMM and attention regardless of shape.
- * Not thread-safe against concurrent compute calls.  Errors: RPO_EINVAL. */
+ * 1 = generic vector-ALU kernels for GEMM and attention regardless of shape,
+ * 16 + k (k = 1..4) = MFMA GEMM with the fixed tile shape of kernel id k (a tuning aid;
+ * attention as in 0).  Not thread-safe against concurrent compute calls.
+ * Errors: RPO_EINVAL. */
 int rpo_set_kernel_path(int path);
 
 /* Per-kernel timing for roofline reports.  rpo_profile_start(kernel_id) makes every later
@@ -44,8 +46,9 @@ int rpo_set_kernel_path(int path);
  * of those launches as the library counts them (GEMM: 2MNK flops, operands + result bytes;
  * decode attention: K/V bytes with a group's shared prefix counted once per group; sampler:
  * the logits rows read once).  Kernel ids:
- *   1  gemm_mfma_kernel<256,256,2,2,..> (M > 512)    2  gemm_mfma_kernel<256,128,2,2,..> (M <= 512)
- *   3  gemm_mfma_kernel<128,128,2,2,..> (M <= 128)   4  gemm_mfma_kernel<64,128,1,2,..>  (M <= 64)
+ *   1  gemm_mfma_kernel<256,256,2,4,..> (prefill-sized problems and wide decode projections)
+ *   2  gemm_mfma_kernel<256,128,2,2,..> (only via rpo_set_kernel_path)
+ *   3  gemm_mfma_kernel<128,128,2,2,..> (decode-sized problems)   4  gemm_mfma_kernel<64,128,1,2,..> (M <= 64)
  *      (all epilogues of a tile shape together; a K-split launch includes its reduction)
  *   7  gemm_generic_kernel      8  attn_decode_mfma_kernel (+ merge)   9  attn_chunk_mfma_kernel
  *   10 sample_kernel

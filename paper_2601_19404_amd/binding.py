@@ -124,8 +124,8 @@ class Model:
         self.handle, self.cfg, self.weights = handle, cfg, weights
 
     def __del__(self):
-        if getattr(self, "handle", None):
-            lib().rpo_model_destroy(self.handle)
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.rpo_model_destroy(self.handle)
             self.handle = None
 
 
@@ -172,8 +172,8 @@ class Batch:
         self.n_groups, self.G, self.max_prefix, self.max_suffix, self.page_tokens, self.max_rows = dims
 
     def __del__(self):
-        if getattr(self, "handle", None):
-            lib().rpo_batch_destroy(self.handle)
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.rpo_batch_destroy(self.handle)
             self.handle = None
 
 

@@ -160,36 +160,54 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_kernel(const bf16* __re
     constexpr int ROWS_PER_PASS = NT / 8;
     const int ld_row = tid >> 3, ld_k = (tid & 7) * 8;
     const bf16* a_base = A + (int64_t)(m0 + ld_row) * lda + ld_k;
-    u32x4_t ra[A_CHUNKS], rb[B_CHUNKS];
+    // Two register sets: while slab kt is multiplied out of LDS, slab kt+1 sits in one set
+    // (about to be written to the other LDS buffer) and slab kt+2 is in flight into the other,
+    // so a global load has two slabs of MFMA work to hide behind.
+    u32x4_t ra0[A_CHUNKS], rb0[B_CHUNKS], ra1[A_CHUNKS], rb1[B_CHUNKS];
     int64_t b_off[B_CHUNKS];  // weight rows are not an arithmetic sequence in SwiGLU order
 #pragma unroll
     for (int i = 0; i < B_CHUNKS; ++i) {
         const int gn = n0 + ld_row + i * ROWS_PER_PASS;
         b_off[i] = gn < N ? (int64_t)weight_row<SWIGLU>(gn, F) * ldw + ld_k : -1;
     }
+    const u32x4_t zero4 = {0u, 0u, 0u, 0u};
 
-#define RPO_LOAD_SLAB(k0)                                                                            \
+#define RPO_LOAD_SLAB(RA, RB, k0)                                                                    \
     {                                                                                                \
         const bool k_ok = (k0) + ld_k < k_end;                                                       \
         _Pragma("unroll") for (int i = 0; i < A_CHUNKS; ++i) {                                       \
             const bool ok = k_ok && (m0 + ld_row + i * ROWS_PER_PASS) < M;                           \
-            ra[i] = ok ? *(const u32x4_t*)(a_base + (int64_t)i * ROWS_PER_PASS * lda + (k0)) : zero4;  \
+            RA[i] = ok ? *(const u32x4_t*)(a_base + (int64_t)i * ROWS_PER_PASS * lda + (k0)) : zero4; \
         }                                                                                            \
         _Pragma("unroll") for (int i = 0; i < B_CHUNKS; ++i) {                                       \
             const bool ok = k_ok && b_off[i] >= 0;                                                   \
-            rb[i] = ok ? *(const u32x4_t*)(W + b_off[i] + (k0)) : zero4;                               \
+            RB[i] = ok ? *(const u32x4_t*)(W + b_off[i] + (k0)) : zero4;                             \
         }                                                                                            \
     }
-#define RPO_STORE_SLAB(buf)                                                                          \
+#define RPO_STORE_SLAB(RA, RB, buf)                                                                  \
     {                                                                                                \
         bf16* as_ = As + (buf) * BM * kLdsRow + ld_row * kLdsRow + ld_k;                             \
         bf16* bs_ = Bs + (buf) * BN * kLdsRow + ld_row * kLdsRow + ld_k;                             \
         _Pragma("unroll") for (int i = 0; i < A_CHUNKS; ++i)                                         \
-            *(u32x4_t*)(as_ + i * ROWS_PER_PASS * kLdsRow) = ra[i];                                    \
+            *(u32x4_t*)(as_ + i * ROWS_PER_PASS * kLdsRow) = RA[i];                                  \
         _Pragma("unroll") for (int i = 0; i < B_CHUNKS; ++i)                                         \
-            *(u32x4_t*)(bs_ + i * ROWS_PER_PASS * kLdsRow) = rb[i];                                    \
+            *(u32x4_t*)(bs_ + i * ROWS_PER_PASS * kLdsRow) = RB[i];                                  \
     }
-    const u32x4_t zero4 = {0u, 0u, 0u, 0u};
+#define RPO_MULTIPLY_SLAB(buf)                                                                       \
+    {                                                                                                \
+        const bf16* as = As + (buf) * BM * kLdsRow + (wm * TM + frag_row) * kLdsRow + frag_k;        \
+        const bf16* bs = Bs + (buf) * BN * kLdsRow + (wn * TN + frag_row) * kLdsRow + frag_k;        \
+        _Pragma("unroll") for (int ks = 0; ks < kBK / 16; ++ks) {                                    \
+            bf16x8_t af[MI], bfr[NI];                                                                \
+            _Pragma("unroll") for (int i = 0; i < MI; ++i)                                           \
+                af[i] = *(const bf16x8_t*)(as + i * 32 * kLdsRow + ks * 16);                         \
+            _Pragma("unroll") for (int j = 0; j < NI; ++j)                                           \
+                bfr[j] = *(const bf16x8_t*)(bs + j * 32 * kLdsRow + ks * 16);                        \
+            _Pragma("unroll") for (int i = 0; i < MI; ++i)                                           \
+                _Pragma("unroll") for (int j = 0; j < NI; ++j)                                       \
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0); \
+        }                                                                                            \
+    }
 
     f32x16_t acc[MI][NI];
 #pragma unroll
@@ -200,36 +218,32 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_kernel(const bf16* __re
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
     const int nk = (k_end - k_begin + kBK - 1) / kBK;
-    if (nk > 0) {
-        RPO_LOAD_SLAB(k_begin);
-        RPO_STORE_SLAB(0);
-    }
-    __syncthreads();
     const int frag_row = lane & 31, frag_k = (lane >> 5) * 8;
-    for (int kt = 0; kt < nk; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < nk) RPO_LOAD_SLAB(k_begin + (kt + 1) * kBK);
-        const bf16* as = As + buf * BM * kLdsRow + (wm * TM + frag_row) * kLdsRow + frag_k;
-        const bf16* bs = Bs + buf * BN * kLdsRow + (wn * TN + frag_row) * kLdsRow + frag_k;
-#pragma unroll
-        for (int ks = 0; ks < kBK / 16; ++ks) {
-            bf16x8_t af[MI], bfr[NI];
-#pragma unroll
-            for (int i = 0; i < MI; ++i) af[i] = *(const bf16x8_t*)(as + i * 32 * kLdsRow + ks * 16);
-#pragma unroll
-            for (int j = 0; j < NI; ++j) bfr[j] = *(const bf16x8_t*)(bs + j * 32 * kLdsRow + ks * 16);
-#pragma unroll
-            for (int i = 0; i < MI; ++i)
-#pragma unroll
-                for (int j = 0; j < NI; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    // slab s lives in LDS buffer s & 1; odd slabs travel through register set 0, even ones
+    // (from slab 2 on) through set 1.
+    if (nk > 0) {
+        RPO_LOAD_SLAB(ra0, rb0, k_begin);
+        RPO_STORE_SLAB(ra0, rb0, 0);
+    }
+    if (nk > 1) RPO_LOAD_SLAB(ra0, rb0, k_begin + kBK);
+    if (nk > 2) RPO_LOAD_SLAB(ra1, rb1, k_begin + 2 * kBK);
+    __syncthreads();
+    for (int kt = 0; kt < nk; kt += 2) {
+        RPO_MULTIPLY_SLAB(0);
+        if (kt + 1 < nk) RPO_STORE_SLAB(ra0, rb0, 1);
+        if (kt + 3 < nk) RPO_LOAD_SLAB(ra0, rb0, k_begin + (kt + 3) * kBK);
+        __syncthreads();
+        if (kt + 1 < nk) {
+            RPO_MULTIPLY_SLAB(1);
+            if (kt + 2 < nk) RPO_STORE_SLAB(ra1, rb1, 0);
+            if (kt + 4 < nk) RPO_LOAD_SLAB(ra1, rb1, k_begin + (kt + 4) * kBK);
         }
-        if (kt + 1 < nk) RPO_STORE_SLAB(buf ^ 1);
         __syncthreads();
     }
 
 #undef RPO_LOAD_SLAB
 #undef RPO_STORE_SLAB
+#undef RPO_MULTIPLY_SLAB
 
     const int col_in = lane & 31, row_in = (lane >> 5) * 4;
     if (EPI == kEpiSwiglu) {
@@ -330,8 +344,19 @@ bool mfma_ok(const GemmArgs& a) {
 }
 
 TileCfg pick_tile(const GemmArgs& a) {
-    if (a.M > 512) return TileCfg{kKidGemm256, 256, 256};
-    if (a.M > 128) return TileCfg{kKidGemm256x128, 256, 128};
+    if (a.path >= 16) {  // tuning aid: a fixed tile shape
+        switch (a.path - 16) {
+            case kKidGemm256: return TileCfg{kKidGemm256, 256, 256};
+            case kKidGemm256x128: return TileCfg{kKidGemm256x128, 256, 128};
+            case kKidGemm128: return TileCfg{kKidGemm128, 128, 128};
+            default: return TileCfg{kKidGemm64, 64, 128};
+        }
+    }
+    // Measured on MI355X: the 8-wave 256x256 tile wins whenever it yields at least ~half a
+    // chip of workgroups; smaller problems do better with 128x128 tiles (two workgroups per
+    // CU) and K splitting.
+    const int t256 = ceil_div(a.M, 256) * ceil_div(a.N, 256);
+    if (a.M > 512 || (a.M > 64 && t256 >= 128)) return TileCfg{kKidGemm256, 256, 256};
     if (a.M > 64) return TileCfg{kKidGemm128, 128, 128};
     return TileCfg{kKidGemm64, 64, 128};
 }
@@ -451,7 +476,7 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
     const int splits = (a.ws && a.ws_bytes) ? pick_splits(a, t) : 1;
     switch (t.id) {
         case kKidGemm256:
-            return launch_tile<256, 256, 2, 2>(a, splits, s);
+            return launch_tile<256, 256, 2, 4>(a, splits, s);
         case kKidGemm256x128:
             return launch_tile<256, 128, 2, 2>(a, splits, s);
         case kKidGemm128:

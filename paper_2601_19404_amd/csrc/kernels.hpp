@@ -45,9 +45,9 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
 // Identifiers of the kernels whose launches can be timed (rpo_profile_start).
 enum KernelId : int {
     kKidNone = 0,
-    kKidGemm256 = 1,        // gemm_mfma_kernel<256,256,2,2,*> (M > 512)
-    kKidGemm256x128 = 2,    // gemm_mfma_kernel<256,128,2,2,*> (128 < M <= 512)
-    kKidGemm128 = 3,        // gemm_mfma_kernel<128,128,2,2,*> (64 < M <= 128)
+    kKidGemm256 = 1,        // gemm_mfma_kernel<256,256,2,4,*> (large problems)
+    kKidGemm256x128 = 2,    // gemm_mfma_kernel<256,128,2,2,*> (tuning aid only)
+    kKidGemm128 = 3,        // gemm_mfma_kernel<128,128,2,2,*> (decode-sized problems, K split)
     kKidGemm64 = 4,         // gemm_mfma_kernel<64,128,1,2,*>  (M <= 64)
     kKidGemmGeneric = 7,
     kKidAttnDecode = 8,     // attn_decode_mfma_kernel

@@ -42,12 +42,13 @@ class RolloutResult:
 
 
 def suffix_rollout(batch: rpo.Batch, prompts, cached, m, temperature: float, seed: int,
-                   seq_ids: torch.Tensor, keep_logits: bool = False, stream=None) -> RolloutResult:
+                   seq_ids: torch.Tensor, keep_logits: bool | int = False, stream=None) -> RolloutResult:
     """Regenerate m_k tokens for each of the G rollouts of every group.
 
     Groups must be ordered by decreasing m (see order_by_suffix_length) so that the
     live rows are always a leading block.  seq_ids: uint64-valued int64 device tensor
-    [B], the Philox stream id of each rollout row."""
+    [B], the Philox stream id of each rollout row.  keep_logits: True keeps a copy of every
+    step's logits (tests), an integer n only those of the first n steps."""
     cfg = batch.model.cfg
     G, ng = batch.G, batch.n_groups
     B = ng * G
@@ -64,6 +65,7 @@ def suffix_rollout(batch: rpo.Batch, prompts, cached, m, temperature: float, see
     out_lp = torch.zeros((max_m, B), dtype=torch.float32, device="cuda")
     row_map = torch.arange(B, dtype=torch.int32, device="cuda") // G
     kept = [] if keep_logits else None
+    n_keep = max_m if keep_logits is True else int(keep_logits)
 
     rpo.rpo_prefill_prefix(batch, tokens_dev, cu, last_logits, stream)
     rpo.rpo_kv_fork(batch, stream)
@@ -73,7 +75,7 @@ def suffix_rollout(batch: rpo.Batch, prompts, cached, m, temperature: float, see
         n0 = live_groups[0] * G
         rpo.rpo_sample(last_logits, ng, V, V, row_map, n0, temperature, seed, seq_ids, 0,
                        out_tokens[0], out_lp[0], stream)
-        if keep_logits:
+        if n_keep > 0:
             kept.append(last_logits.clone())
     for j in range(1, max_m):
         n = live_groups[j] * G
@@ -82,7 +84,7 @@ def suffix_rollout(batch: rpo.Batch, prompts, cached, m, temperature: float, see
         rpo.rpo_decode_step(batch, out_tokens[j - 1], n, None, logits, stream)
         rpo.rpo_sample(logits, n, V, V, None, n, temperature, seed, seq_ids, j, out_tokens[j],
                        out_lp[j], stream)
-        if keep_logits:
+        if j < n_keep:
             kept.append(logits[:n].clone())
     return RolloutResult(out_tokens.t().contiguous(), out_lp.t().contiguous(), m, cu,
                          int(m.sum()) * G, kept)

@@ -239,3 +239,35 @@ def test_teacher_forced_rows_and_suffix_logprobs(tiny):
         ref = torch.log_softmax(torch.from_numpy(full[18:25]) / temp, -1).numpy()[np.arange(7), suffix]
         np.testing.assert_allclose(lp, ref, atol=1e-10)
     assert T.suffix_logprobs(shape, w, prefix, suffix[:0]).shape == (0,)
+
+
+def test_round_bf16_matches_library_and_hand_values():
+    rng = np.random.default_rng(11)
+    x = np.concatenate([rng.normal(size=5000) * 10.0 ** rng.integers(-6, 6, size=5000),
+                        [0.0, -0.0, 1.0, -1.0, 3.0e38, 1e-40]])
+    ref = torch.from_numpy(x.astype(np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+    np.testing.assert_array_equal(T.round_bf16(x), ref)
+    # ties go to the even significand; anything above the tie goes up
+    assert T.round_bf16(np.array([1.0 + 2.0 ** -8]))[0] == 1.0
+    assert T.round_bf16(np.array([1.0 + 2.0 ** -7 + 2.0 ** -8]))[0] == 1.0 + 2.0 ** -6
+    assert T.round_bf16(np.array([1.0 + 2.0 ** -8 + 2.0 ** -20]))[0] == 1.0 + 2.0 ** -7
+    y = T.round_bf16(x)
+    np.testing.assert_array_equal(T.round_bf16(y), y)            # idempotent
+    assert np.isnan(T.round_bf16(np.array([np.nan]))[0]) and np.isinf(T.round_bf16(np.array([np.inf]))[0])
+
+
+def test_bf16_storage_mode_is_a_small_perturbation_and_consistent(tiny):
+    """Quantising the stored tensors moves the logits by about 2^-9 relative (not more: a
+    misplaced rounding of an accumulator would), and the two evaluation orders still agree
+    exactly enough (same values are rounded in both)."""
+    shape, w = tiny
+    sb = T.Shape(**{**shape.__dict__, "storage": "bf16"})
+    toks = np.random.default_rng(12).integers(0, shape.vocab, size=24)
+    exact = T.logits_full(shape, w, toks)
+    quant = T.logits_full(sb, w, toks)
+    err = np.abs(quant - exact).max() / exact.std()
+    assert 1e-4 < err < 5e-2
+    kv, z = T.prefill(sb, w, toks[:17])
+    np.testing.assert_allclose(z, quant[16], atol=1e-9)
+    for j in range(17, 24):
+        np.testing.assert_allclose(T.decode_step(sb, w, int(toks[j]), kv), quant[j], atol=1e-9)

@@ -8,9 +8,14 @@ from oracle import transformer as T
 from paper_2601_19404_amd import synth
 
 
-def oracle_shape(cfg: synth.ModelCfg, n_layers=None) -> T.Shape:
+def oracle_shape(cfg: synth.ModelCfg, n_layers=None, storage="f64") -> T.Shape:
+    """storage="model": the precision the model stores its activations / KV in (bf16 models
+    quantise them, fp32 models are compared with the exact fp64 forward)."""
+    if storage == "model":
+        storage = "bf16" if cfg.dtype == "bf16" else "f64"
     return T.Shape(cfg.n_layers if n_layers is None else n_layers, cfg.d_model, cfg.n_q_heads,
-                   cfg.n_kv_heads, cfg.head_dim, cfg.d_ffn, cfg.vocab, cfg.rope_base, cfg.rms_eps)
+                   cfg.n_kv_heads, cfg.head_dim, cfg.d_ffn, cfg.vocab, cfg.rope_base, cfg.rms_eps,
+                   storage)
 
 
 def to_device(w: dict) -> dict:
