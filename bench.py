@@ -68,7 +68,7 @@ def one_step(st, seed: int):
     return res
 
 
-def cpu_baseline(st, budget_tokens: int = 4, prefix_cap: int = 256, n_rollouts: int = 2):
+def cpu_baseline(st, budget_tokens: int = 6, prefix_cap: int = 256, n_rollouts: int = 3):
     """The fp64 oracle on the host cores, on a bounded slice of the same workload: group 0,
     its prefix cut to the last `prefix_cap` tokens, `n_rollouts` rollouts, `budget_tokens`
     regenerated tokens each."""

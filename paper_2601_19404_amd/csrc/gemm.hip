@@ -130,8 +130,8 @@ template <int BM, int BN, int WM, int WN, int EPI, bool SWIGLU>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_kernel(const bf16* __restrict__ A, int64_t lda,
                                                                 const bf16* __restrict__ W, int64_t ldw,
                                                                 void* __restrict__ Cv, int64_t ldc,
-                                                                int M, int N, int K, int grid_m, int n_tiles,
-                                                                int k_per_split, int F) {
+                                                                int M, int N, int K, int grid_m, int grid_n,
+                                                                int n_tiles, int k_per_split, int F) {
     constexpr int NT = WM * WN * 64;
     constexpr int TM = BM / WM, TN = BN / WN;
     constexpr int MI = TM / 32, NI = TN / 32;
@@ -144,12 +144,20 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_kernel(const bf16* __re
     bf16* As = (bf16*)smem_raw;                 // [2][BM][kLdsRow]
     bf16* Bs = As + 2 * BM * kLdsRow;           // [2][BN][kLdsRow]
 
-    // Tile order: ids handed to one XCD (i % 8 == x) form one contiguous run of logical tiles,
-    // and logical tiles walk down M first, so the row tiles sharing a weight tile hit one L2.
+    // Tile order.  Workgroup ids are dealt round-robin to the 8 XCDs, so the ids one XCD sees
+    // (i % 8 == x) are mapped to one contiguous run of logical tiles.  Logical tiles are grouped
+    // in blocks of blk_m x blk_n = 32 tiles (one per CU of an XCD): the workgroups running
+    // together on an XCD then share blk_m row slabs and blk_n weight slabs through its L2.
     const int per_xcd = (n_tiles + kXcd - 1) / kXcd;
     const int logical = (blockIdx.x % kXcd) * per_xcd + blockIdx.x / kXcd;
     if (logical >= n_tiles) return;
-    const int bm = logical % grid_m, bn = logical / grid_m;
+    const int blk_m = grid_m < 8 ? grid_m : 8;
+    const int blk_n = 32 / blk_m;
+    const int blocks_m = (grid_m + blk_m - 1) / blk_m;
+    const int blk = logical / (blk_m * blk_n), in_blk = logical % (blk_m * blk_n);
+    const int bm = (blk % blocks_m) * blk_m + in_blk % blk_m;
+    const int bn = (blk / blocks_m) * blk_n + in_blk / blk_m;
+    if (bm >= grid_m || bn >= grid_n) return;
     const int m0 = bm * BM, n0 = bn * BN;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave % WM, wn = wave / WM;
@@ -157,31 +165,39 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_kernel(const bf16* __re
     const int k_end = min(K, k_begin + k_per_split);
 
     // Thread t moves the 16-byte piece (row t / 8 + i * NT / 8, k-chunk t % 8) of each slab.
+    // Loads are unconditional (rows beyond M / N are clamped to the last row: their products
+    // are never stored; a K tail is zeroed by a select), so the compiler can count the loads in
+    // flight and wait only for the older register set.
     constexpr int ROWS_PER_PASS = NT / 8;
     const int ld_row = tid >> 3, ld_k = (tid & 7) * 8;
-    const bf16* a_base = A + (int64_t)(m0 + ld_row) * lda + ld_k;
     // Two register sets: while slab kt is multiplied out of LDS, slab kt+1 sits in one set
     // (about to be written to the other LDS buffer) and slab kt+2 is in flight into the other,
     // so a global load has two slabs of MFMA work to hide behind.
     u32x4_t ra0[A_CHUNKS], rb0[B_CHUNKS], ra1[A_CHUNKS], rb1[B_CHUNKS];
-    int64_t b_off[B_CHUNKS];  // weight rows are not an arithmetic sequence in SwiGLU order
+    int64_t a_off[A_CHUNKS], b_off[B_CHUNKS];
+#pragma unroll
+    for (int i = 0; i < A_CHUNKS; ++i) {
+        const int gm = min(m0 + ld_row + i * ROWS_PER_PASS, M - 1);
+        a_off[i] = (int64_t)gm * lda;
+    }
 #pragma unroll
     for (int i = 0; i < B_CHUNKS; ++i) {
-        const int gn = n0 + ld_row + i * ROWS_PER_PASS;
-        b_off[i] = gn < N ? (int64_t)weight_row<SWIGLU>(gn, F) * ldw + ld_k : -1;
+        const int gn = min(n0 + ld_row + i * ROWS_PER_PASS, N - 1);
+        b_off[i] = (int64_t)weight_row<SWIGLU>(gn, F) * ldw;
     }
     const u32x4_t zero4 = {0u, 0u, 0u, 0u};
 
 #define RPO_LOAD_SLAB(RA, RB, k0)                                                                    \
     {                                                                                                \
         const bool k_ok = (k0) + ld_k < k_end;                                                       \
+        const int kk = k_ok ? (k0) + ld_k : k_end - 8;                                               \
         _Pragma("unroll") for (int i = 0; i < A_CHUNKS; ++i) {                                       \
-            const bool ok = k_ok && (m0 + ld_row + i * ROWS_PER_PASS) < M;                           \
-            RA[i] = ok ? *(const u32x4_t*)(a_base + (int64_t)i * ROWS_PER_PASS * lda + (k0)) : zero4; \
+            const u32x4_t v = *(const u32x4_t*)(A + a_off[i] + kk);                                  \
+            RA[i] = k_ok ? v : zero4;                                                                \
         }                                                                                            \
         _Pragma("unroll") for (int i = 0; i < B_CHUNKS; ++i) {                                       \
-            const bool ok = k_ok && b_off[i] >= 0;                                                   \
-            RB[i] = ok ? *(const u32x4_t*)(W + b_off[i] + (k0)) : zero4;                             \
+            const u32x4_t v = *(const u32x4_t*)(W + b_off[i] + kk);                                  \
+            RB[i] = k_ok ? v : zero4;                                                                \
         }                                                                                            \
     }
 #define RPO_STORE_SLAB(RA, RB, buf)                                                                  \
@@ -220,26 +236,30 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_kernel(const bf16* __re
     const int nk = (k_end - k_begin + kBK - 1) / kBK;
     const int frag_row = lane & 31, frag_k = (lane >> 5) * 8;
     // slab s lives in LDS buffer s & 1; odd slabs travel through register set 0, even ones
-    // (from slab 2 on) through set 1.
+    // (from slab 2 on) through set 1.  Loads are issued unconditionally (past the last slab
+    // they re-read it and the data is dropped) so that every wait for a register set can
+    // leave exactly the other set's loads in flight.
+#define RPO_SLAB_K(s_) (k_begin + ((s_) < nk ? (s_) : nk - 1) * kBK)
     if (nk > 0) {
         RPO_LOAD_SLAB(ra0, rb0, k_begin);
         RPO_STORE_SLAB(ra0, rb0, 0);
-    }
-    if (nk > 1) RPO_LOAD_SLAB(ra0, rb0, k_begin + kBK);
-    if (nk > 2) RPO_LOAD_SLAB(ra1, rb1, k_begin + 2 * kBK);
-    __syncthreads();
-    for (int kt = 0; kt < nk; kt += 2) {
-        RPO_MULTIPLY_SLAB(0);
-        if (kt + 1 < nk) RPO_STORE_SLAB(ra0, rb0, 1);
-        if (kt + 3 < nk) RPO_LOAD_SLAB(ra0, rb0, k_begin + (kt + 3) * kBK);
+        RPO_LOAD_SLAB(ra0, rb0, RPO_SLAB_K(1));
+        RPO_LOAD_SLAB(ra1, rb1, RPO_SLAB_K(2));
         __syncthreads();
-        if (kt + 1 < nk) {
-            RPO_MULTIPLY_SLAB(1);
-            if (kt + 2 < nk) RPO_STORE_SLAB(ra1, rb1, 0);
-            if (kt + 4 < nk) RPO_LOAD_SLAB(ra1, rb1, k_begin + (kt + 4) * kBK);
+        for (int kt = 0; kt < nk; kt += 2) {
+            RPO_MULTIPLY_SLAB(0);
+            if (kt + 1 < nk) RPO_STORE_SLAB(ra0, rb0, 1);
+            RPO_LOAD_SLAB(ra0, rb0, RPO_SLAB_K(kt + 3));
+            __syncthreads();
+            if (kt + 1 < nk) {
+                RPO_MULTIPLY_SLAB(1);
+                if (kt + 2 < nk) RPO_STORE_SLAB(ra1, rb1, 0);
+            }
+            RPO_LOAD_SLAB(ra1, rb1, RPO_SLAB_K(kt + 4));
+            __syncthreads();
         }
-        __syncthreads();
     }
+#undef RPO_SLAB_K
 
 #undef RPO_LOAD_SLAB
 #undef RPO_STORE_SLAB
@@ -365,7 +385,7 @@ TileCfg pick_tile(const GemmArgs& a) {
 // too few, and only when the workspace can hold the partials.
 int pick_splits(const GemmArgs& a, const TileCfg& t) {
     const int tiles = ceil_div(a.M, t.bm) * ceil_div(a.N, t.bn);
-    if (tiles >= 192 || a.K < 1024) return 1;
+    if (tiles >= 128 || a.K < 1024) return 1;  // half a chip of tiles: splitting costs more than it gains
     int splits = ceil_div(256, tiles);
     const int max_by_k = a.K / 512;  // at least 8 slabs per split
     splits = splits < max_by_k ? splits : max_by_k;
@@ -377,7 +397,9 @@ int pick_splits(const GemmArgs& a, const TileCfg& t) {
 template <int BM, int BN, int WM, int WN, int EPI, bool SWIGLU>
 hipError_t launch_one(const GemmArgs& a, int splits, void* out, hipStream_t s) {
     const int gm = ceil_div(a.M, BM), gn = ceil_div(a.N, BN);
-    const int n_tiles = gm * gn;
+    // logical tile space padded to whole blocks of blk_m x blk_n tiles (see the kernel)
+    const int blk_m = gm < 8 ? gm : 8, blk_n = 32 / blk_m;
+    const int n_tiles = ceil_div(gm, blk_m) * ceil_div(gn, blk_n) * blk_m * blk_n;
     const int per_xcd = ceil_div(n_tiles, kXcd);
     const size_t lds = (size_t)2 * (BM + BN) * kLdsRow * sizeof(bf16);
     auto kern = gemm_mfma_kernel<BM, BN, WM, WN, EPI, SWIGLU>;
@@ -390,7 +412,7 @@ hipError_t launch_one(const GemmArgs& a, int splits, void* out, hipStream_t s) {
     int k_per_split = ceil_div(ceil_div(a.K, splits), kBK) * kBK;
     const dim3 grid((unsigned)(per_xcd * kXcd), (unsigned)splits), block(WM * WN * 64);
     kern<<<grid, block, lds, s>>>((const bf16*)a.A, a.lda, (const bf16*)a.W, a.ldw, out, a.ldc, a.M, a.N, a.K,
-                                  gm, n_tiles, k_per_split, a.N / 2);
+                                  gm, gn, n_tiles, k_per_split, a.N / 2);
     return hipGetLastError();
 }
 
