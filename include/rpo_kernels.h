@@ -34,6 +34,8 @@ int rpo_gemm_nt(const void *a_dev, int64_t lda, const void *w_dev, int64_t ldw, 
 
 /* Process-wide kernel selection: 0 = fastest available kernel for the shape (default),
  * 1 = generic vector-ALU kernels for GEMM and attention regardless of shape,
+ * 2 = MFMA GEMM with register-staged LDS fills instead of direct-to-LDS loads (the
+ *     fallback used when K is not a multiple of 64; selectable for comparison),
  * 16 + k (k = 1..4) = MFMA GEMM with the fixed tile shape of kernel id k (a tuning aid;
  * attention as in 0).  Not thread-safe against concurrent compute calls.
  * Errors: RPO_EINVAL. */

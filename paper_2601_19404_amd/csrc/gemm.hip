@@ -101,6 +101,56 @@ __global__ __launch_bounds__(256) void gemm_generic_swiglu_kernel(const T* __res
     C[(int64_t)m * ldc + j] = from_f32<T>(g / (1.0f + expf(-g)) * u);
 }
 
+// Epilogue shared by the MFMA kernels: lane l holds column (l % 32) and rows
+// 8 * (e / 4) + 4 * (l / 32) + (e % 4) of each 32x32 block.
+template <int MI, int NI, int TM, int TN, int EPI>
+__device__ inline void gemm_epilogue(f32x16_t (&acc)[MI][NI], void* __restrict__ Cv, int64_t ldc, int M, int N,
+                                     int m0, int n0, int wm, int wn, int lane) {
+    const int col_in = lane & 31, row_in = (lane >> 5) * 4;
+    if (EPI == kEpiSwiglu) {
+        // blocks (j, j + 1) = (gate, up) of output columns (n0 + wn*TN)/2 + (j/2)*32 + col_in
+        bf16* C = (bf16*)Cv;
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; j += 2) {
+                const int vn = n0 + wn * TN + j * 32;  // virtual column of the gate block
+                if (vn + col_in >= N) continue;         // N = 2F is a multiple of 64: pairs are whole
+                const int oc = (vn >> 1) + col_in;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int gm = m0 + wm * TM + i * 32 + 8 * (e >> 2) + row_in + (e & 3);
+                    if (gm >= M) continue;
+                    C[(int64_t)gm * ldc + oc] = f32_to_bf16(silu_f(acc[i][j][e]) * acc[i][j + 1][e]);
+                }
+            }
+        return;
+    }
+    float* Cp = (float*)Cv + (EPI == kEpiPartial ? (int64_t)blockIdx.y * M * (int64_t)N : 0);
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            const int gn = n0 + wn * TN + j * 32 + col_in;
+            if (gn >= N) continue;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int gm = m0 + wm * TM + i * 32 + 8 * (e >> 2) + row_in + (e & 3);
+                if (gm >= M) continue;
+                const float v = acc[i][j][e];
+                if (EPI == kEpiStore)
+                    ((bf16*)Cv)[(int64_t)gm * ldc + gn] = f32_to_bf16(v);
+                else if (EPI == kEpiStoreF32)
+                    ((float*)Cv)[(int64_t)gm * ldc + gn] = v;
+                else if (EPI == kEpiAddF32)
+                    ((float*)Cv)[(int64_t)gm * ldc + gn] += v;
+                else
+                    Cp[(int64_t)gm * N + gn] = v;
+            }
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------
 // MFMA kernel.
 //
@@ -265,49 +315,140 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_kernel(const bf16* __re
 #undef RPO_STORE_SLAB
 #undef RPO_MULTIPLY_SLAB
 
-    const int col_in = lane & 31, row_in = (lane >> 5) * 4;
-    if (EPI == kEpiSwiglu) {
-        // blocks (j, j + 1) = (gate, up) of output columns (n0 + wn*TN)/2 + (j/2)*32 + col_in
-        bf16* C = (bf16*)Cv;
+    gemm_epilogue<MI, NI, TM, TN, EPI>(acc, Cv, ldc, M, N, m0, n0, wm, wn, lane);
+}
+
+// ---------------------------------------------------------------------------
+// MFMA kernel, direct-to-LDS variant (K a multiple of 64).
+//
+// Same tiling and epilogues as gemm_mfma_kernel, but the slabs never pass through
+// registers: each lane issues global_load_lds_dwordx4, which writes 16 bytes straight
+// into LDS at M0 + 16 * lane.  A wave instruction therefore fills 1 KiB = 8 rows of an
+// UNPADDED [rows][64] bf16 stage; bank conflicts of the fragment reads are avoided by
+// permuting the eight 16-byte pieces of a row: piece p of row r is stored at position
+// p ^ g(r), g(r) = (r & 7) ^ ((r >> 3) & 1) (the lane picks its global source piece
+// accordingly).  Two LDS stages: the loads of slab kt+1 are issued right after the
+// barrier that retires slab kt-1 and land while slab kt is multiplied.  The loads are
+// inline assembly (the compiler's own wait-count pass would otherwise wait for every
+// outstanding LDS-writing load before each LDS read), so the waits are explicit.
+// ---------------------------------------------------------------------------
+__device__ inline void dma_load16(const void* gptr, uint32_t lds_byte_addr) {
+    asm volatile(
+        "s_mov_b32 m0, %1\n\t"
+        "s_nop 0\n\t"
+        "global_load_lds_dwordx4 %0, off\n\t"
+        :
+        : "v"(gptr), "s"(lds_byte_addr)
+        : "memory");
+}
+
+template <int BM, int BN, int WM, int WN, int EPI, bool SWIGLU>
+__global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const bf16* __restrict__ A, int64_t lda,
+                                                               const bf16* __restrict__ W, int64_t ldw,
+                                                               void* __restrict__ Cv, int64_t ldc, int M,
+                                                               int N, int K, int grid_m, int grid_n,
+                                                               int n_tiles, int k_per_split, int F) {
+    constexpr int NW = WM * WN;
+    constexpr int TM = BM / WM, TN = BN / WN;
+    constexpr int MI = TM / 32, NI = TN / 32;
+    constexpr int A_INST = BM / 8 / NW;  // wave instructions per slab (8 rows each)
+    constexpr int B_INST = BN / 8 / NW;
+    constexpr int A_STAGE = BM * kBK, B_STAGE = BN * kBK;  // elements
+    static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile/wave mismatch");
+    static_assert(!SWIGLU || NI % 2 == 0, "SwiGLU needs gate/up block pairs inside a wave");
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    bf16* As = (bf16*)smem_raw;        // [2][BM][64]
+    bf16* Bs = As + 2 * A_STAGE;       // [2][BN][64]
+    const uint32_t lds_a = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem_raw;
+    const uint32_t lds_b = lds_a + 2 * A_STAGE * 2;
+
+    const int per_xcd = (n_tiles + kXcd - 1) / kXcd;
+    const int logical = (blockIdx.x % kXcd) * per_xcd + blockIdx.x / kXcd;
+    if (logical >= n_tiles) return;
+    const int blk_m = grid_m < 8 ? grid_m : 8;
+    const int blk_n = 32 / blk_m;
+    const int blocks_m = (grid_m + blk_m - 1) / blk_m;
+    const int blk = logical / (blk_m * blk_n), in_blk = logical % (blk_m * blk_n);
+    const int bm = (blk % blocks_m) * blk_m + in_blk % blk_m;
+    const int bn = (blk / blocks_m) * blk_n + in_blk / blk_m;
+    if (bm >= grid_m || bn >= grid_n) return;
+    const int m0 = bm * BM, n0 = bn * BN;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave % WM, wn = wave / WM;
+    const int k_begin = blockIdx.y * k_per_split;
+    const int k_end = min(K, k_begin + k_per_split);
+    const int nk = (k_end - k_begin) / kBK;
+
+    // Load addressing.  Instruction j of this wave fills row group rg = j * NW + wave
+    // (rows 8 rg .. 8 rg + 7); this lane's row is 8 rg + lane / 8 and it stores at position
+    // lane % 8, i.e. it fetches piece (lane % 8) ^ g(row).
+    const bf16* a_src[A_INST];
+    const bf16* b_src[B_INST];
 #pragma unroll
-        for (int i = 0; i < MI; ++i)
-#pragma unroll
-            for (int j = 0; j < NI; j += 2) {
-                const int vn = n0 + wn * TN + j * 32;  // virtual column of the gate block
-                if (vn + col_in >= N) continue;         // N = 2F is a multiple of 64: pairs are whole
-                const int oc = (vn >> 1) + col_in;
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int gm = m0 + wm * TM + i * 32 + 8 * (e >> 2) + row_in + (e & 3);
-                    if (gm >= M) continue;
-                    C[(int64_t)gm * ldc + oc] = f32_to_bf16(silu_f(acc[i][j][e]) * acc[i][j + 1][e]);
-                }
-            }
-        return;
+    for (int j = 0; j < A_INST; ++j) {
+        const int rg = j * NW + wave;
+        const int row = rg * 8 + (lane >> 3);
+        const int piece = (lane & 7) ^ (lane >> 3) ^ (rg & 1);
+        a_src[j] = A + (int64_t)min(m0 + row, M - 1) * lda + piece * 8 + k_begin;
     }
-    float* Cp = (float*)Cv + (EPI == kEpiPartial ? (int64_t)blockIdx.y * M * (int64_t)N : 0);
 #pragma unroll
-    for (int i = 0; i < MI; ++i) {
+    for (int j = 0; j < B_INST; ++j) {
+        const int rg = j * NW + wave;
+        const int row = rg * 8 + (lane >> 3);
+        const int piece = (lane & 7) ^ (lane >> 3) ^ (rg & 1);
+        b_src[j] = W + (int64_t)weight_row<SWIGLU>(min(n0 + row, N - 1), F) * ldw + piece * 8 + k_begin;
+    }
+#define RPO_DMA_SLAB(stage, kt_)                                                                        \
+    {                                                                                                   \
+        _Pragma("unroll") for (int j = 0; j < A_INST; ++j)                                              \
+            dma_load16(a_src[j] + (kt_) * kBK, lds_a + ((stage) * A_STAGE + (j * NW + wave) * 512) * 2); \
+        _Pragma("unroll") for (int j = 0; j < B_INST; ++j)                                              \
+            dma_load16(b_src[j] + (kt_) * kBK, lds_b + ((stage) * B_STAGE + (j * NW + wave) * 512) * 2); \
+    }
+
+    f32x16_t acc[MI][NI];
 #pragma unroll
-        for (int j = 0; j < NI; ++j) {
-            const int gn = n0 + wn * TN + j * 32 + col_in;
-            if (gn >= N) continue;
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int gm = m0 + wm * TM + i * 32 + 8 * (e >> 2) + row_in + (e & 3);
-                if (gm >= M) continue;
-                const float v = acc[i][j][e];
-                if (EPI == kEpiStore)
-                    ((bf16*)Cv)[(int64_t)gm * ldc + gn] = f32_to_bf16(v);
-                else if (EPI == kEpiStoreF32)
-                    ((float*)Cv)[(int64_t)gm * ldc + gn] = v;
-                else if (EPI == kEpiAddF32)
-                    ((float*)Cv)[(int64_t)gm * ldc + gn] += v;
-                else
-                    Cp[(int64_t)gm * N + gn] = v;
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+    // Fragment addressing: row = 32-aligned base + lane % 32, so g(row) depends on the lane only.
+    const int frag_row = lane & 31;
+    const int frag_g = (lane & 7) ^ ((lane >> 3) & 1);
+    const int frag_half = lane >> 5;
+    if (nk > 0) {
+        RPO_DMA_SLAB(0, 0);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        for (int kt = 0; kt < nk; ++kt) {
+            const int stage = kt & 1;
+            if (kt + 1 < nk) RPO_DMA_SLAB(stage ^ 1, kt + 1);
+            const bf16* as = As + stage * A_STAGE + (wm * TM + frag_row) * kBK;
+            const bf16* bs = Bs + stage * B_STAGE + (wn * TN + frag_row) * kBK;
+#pragma unroll
+            for (int ks = 0; ks < kBK / 16; ++ks) {
+                const int piece = ((ks * 2 + frag_half) ^ frag_g) * 8;
+                bf16x8_t af[MI], bfr[NI];
+#pragma unroll
+                for (int i = 0; i < MI; ++i) af[i] = *(const bf16x8_t*)(as + i * 32 * kBK + piece);
+#pragma unroll
+                for (int j = 0; j < NI; ++j) bfr[j] = *(const bf16x8_t*)(bs + j * 32 * kBK + piece);
+#pragma unroll
+                for (int i = 0; i < MI; ++i)
+#pragma unroll
+                    for (int j = 0; j < NI; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
             }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
         }
     }
+#undef RPO_DMA_SLAB
+    gemm_epilogue<MI, NI, TM, TN, EPI>(acc, Cv, ldc, M, N, m0, n0, wm, wn, lane);
 }
 
 // Sum the K-split partials [splits][M][N] and apply the epilogue.  One thread per output
@@ -401,16 +542,31 @@ hipError_t launch_one(const GemmArgs& a, int splits, void* out, hipStream_t s) {
     const int blk_m = gm < 8 ? gm : 8, blk_n = 32 / blk_m;
     const int n_tiles = ceil_div(gm, blk_m) * ceil_div(gn, blk_n) * blk_m * blk_n;
     const int per_xcd = ceil_div(n_tiles, kXcd);
+    const int k_per_split = ceil_div(ceil_div(a.K, splits), kBK) * kBK;
+    const dim3 grid((unsigned)(per_xcd * kXcd), (unsigned)splits), block(WM * WN * 64);
+    // direct-to-LDS loads need whole 64-deep slabs; path 2 keeps the register-staged kernel
+    const bool dma = a.K % kBK == 0 && a.path != 2;
+    if (dma) {
+        const size_t lds = (size_t)2 * (BM + BN) * kBK * sizeof(bf16);
+        auto kern = gemm_dma_kernel<BM, BN, WM, WN, EPI, SWIGLU>;
+        static bool attr_set = false;  // one flag per template instance
+        if (!attr_set) {
+            hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            attr_set = true;
+        }
+        kern<<<grid, block, lds, s>>>((const bf16*)a.A, a.lda, (const bf16*)a.W, a.ldw, out, a.ldc, a.M, a.N, a.K,
+                                      gm, gn, n_tiles, k_per_split, a.N / 2);
+        return hipGetLastError();
+    }
     const size_t lds = (size_t)2 * (BM + BN) * kLdsRow * sizeof(bf16);
     auto kern = gemm_mfma_kernel<BM, BN, WM, WN, EPI, SWIGLU>;
-    static bool attr_set = false;  // one flag per template instance
+    static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    int k_per_split = ceil_div(ceil_div(a.K, splits), kBK) * kBK;
-    const dim3 grid((unsigned)(per_xcd * kXcd), (unsigned)splits), block(WM * WN * 64);
     kern<<<grid, block, lds, s>>>((const bf16*)a.A, a.lda, (const bf16*)a.W, a.ldw, out, a.ldc, a.M, a.N, a.K,
                                   gm, gn, n_tiles, k_per_split, a.N / 2);
     return hipGetLastError();

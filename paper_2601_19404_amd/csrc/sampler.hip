@@ -50,11 +50,25 @@ __device__ inline uint64_t weight_u64(float z, float zmax, float inv_t) {
     p = __fadd_rn(__fmul_rn(p, f), 0x1.ebfbe0p-3f);
     p = __fadd_rn(__fmul_rn(p, f), 0x1.62e430p-1f);
     p = __fadd_rn(__fmul_rn(p, f), 1.0f);
-    // p in (0.7, 1.42), exponent e = n + 40 in [-1, 40]: p * 2^e < 2^41 is exact in fp64.
-    const double v = ldexp((double)p, (int)n + 40);
-    return (uint64_t)v;  // truncation toward zero == floor for v >= 0
+    // p = m * 2^(E - 23) with a 24-bit integer m and E in {-1, 0}; floor(p * 2^(n + 40)) is a shift
+    // of m by E - 23 + n + 40 in [-25, 17] (exact integer arithmetic, truncation == floor).
+    const uint32_t bits = __float_as_uint(p);
+    const uint32_t m = (bits & 0x7fffffu) | 0x800000u;
+    const int sh = (int)(bits >> 23) - 127 - 23 + (int)n + 40;
+    return sh >= 0 ? ((uint64_t)m << sh) : (uint64_t)(m >> (-sh));
 }
 
+// Sum over the wave of values < 2^45: two 32-bit sums (low 22 bits, high bits) so each
+// cross-lane step moves one register.
+__device__ inline uint64_t wave_sum_u45(uint64_t v) {
+    uint32_t lo = (uint32_t)v & 0x3fffffu, hi = (uint32_t)(v >> 22);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        lo += __shfl_xor(lo, o, kWave);
+        hi += __shfl_xor(hi, o, kWave);
+    }
+    return ((uint64_t)hi << 22) + lo;
+}
 __device__ inline uint64_t wave_sum_u64(uint64_t v) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
@@ -65,38 +79,60 @@ __device__ inline uint64_t wave_sum_u64(uint64_t v) {
     return v;
 }
 
-// One workgroup (4 waves) per output row.  The row is cut into segments of 256
-// logits (4 per lane); wave w owns segments w, w + 4, ...  Integer sums make the
-// result independent of this decomposition.
-constexpr int kSegLen = 256;
-constexpr int kMaxSeg = 1024;  // vocab <= 262144
+// Four consecutive logits starting at i (values beyond V read as -inf); one 16-byte load when
+// the row allows it.
+__device__ inline float4 load4(const float* z, int i, int V, bool vec) {
+    if (vec && i + 3 < V) return *(const float4*)(z + i);
+    float4 r;
+    r.x = i < V ? z[i] : -INFINITY;
+    r.y = i + 1 < V ? z[i + 1] : -INFINITY;
+    r.z = i + 2 < V ? z[i + 2] : -INFINITY;
+    r.w = i + 3 < V ? z[i + 3] : -INFINITY;
+    return r;
+}
+
+// One workgroup (4 waves) per output row.  The row is cut into segments of 1024 logits =
+// 4 sub-blocks of 256 (4 per lane); wave w owns segments w, w + 4, ...  Integer sums make
+// the result independent of this decomposition.
+constexpr int kSubLen = 256;
+constexpr int kSegLen = 1024;
+constexpr int kMaxSeg = 256;  // vocab <= 262144
 
 __global__ __launch_bounds__(256) void sample_kernel(SampleArgs a) {
     __shared__ uint64_t seg_sum[kMaxSeg];
     __shared__ float red[4];
     __shared__ int pick_seg;
-    __shared__ uint64_t pick_rem;
+    __shared__ uint64_t pick_rem, row_total;
     const int r = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int src = a.row_map ? a.row_map[r] : r;
     const float* z = a.logits + (int64_t)src * a.row_stride;
     const int V = a.vocab;
     const int n_seg = (V + kSegLen - 1) / kSegLen;
+    const bool vec = ((uintptr_t)z % 16) == 0;
 
     float zmax = -INFINITY;
-    for (int i = tid; i < V; i += 256) zmax = fmaxf(zmax, z[i]);
+    for (int i = tid * 4; i < V; i += 1024) {
+        const float4 v = load4(z, i, V, vec);
+        zmax = fmaxf(fmaxf(zmax, fmaxf(v.x, v.y)), fmaxf(v.z, v.w));
+    }
     zmax = wave_max(zmax);
     if (lane == 0) red[wave] = zmax;
     __syncthreads();
     zmax = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
 
     for (int sg = wave; sg < n_seg; sg += 4) {
-        const int i0 = sg * kSegLen + lane * 4;
-        uint64_t q = 0;
+        uint64_t q = 0;  // < 16 * 2^41
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-            if (i0 + e < V) q += weight_u64(z[i0 + e], zmax, a.inv_t);
-        q = wave_sum_u64(q);
+        for (int sb = 0; sb < 4; ++sb) {
+            const int i0 = sg * kSegLen + sb * kSubLen + lane * 4;
+            if (i0 < V) {
+                const float4 v = load4(z, i0, V, vec);
+                q += weight_u64(v.x, zmax, a.inv_t) + weight_u64(v.y, zmax, a.inv_t) +
+                     weight_u64(v.z, zmax, a.inv_t) + weight_u64(v.w, zmax, a.inv_t);
+            }
+        }
+        q = wave_sum_u45(q);
         if (lane == 0) seg_sum[sg] = q;
     }
     __syncthreads();
@@ -117,49 +153,54 @@ __global__ __launch_bounds__(256) void sample_kernel(SampleArgs a) {
             }
             pick_seg = sg;
             pick_rem = t - run;  // < seg_sum[sg]
+            row_total = total;
         }
     }
     __syncthreads();
     if (wave == 0) {
-        const int sg = pick_seg;
-        const uint64_t rem = pick_rem;
-        const int i0 = sg * kSegLen + lane * 4;
-        uint64_t q[4];
-        uint64_t mine = 0;
+        uint64_t rem = pick_rem;
+        // walk the 4 sub-blocks of the chosen segment in vocabulary order
+        for (int sb = 0; sb < 4; ++sb) {
+            const int i0 = pick_seg * kSegLen + sb * kSubLen + lane * 4;
+            const float4 v = load4(z, i0, V, vec);
+            uint64_t q[4];
+            q[0] = weight_u64(v.x, zmax, a.inv_t);
+            q[1] = weight_u64(v.y, zmax, a.inv_t);
+            q[2] = weight_u64(v.z, zmax, a.inv_t);
+            q[3] = weight_u64(v.w, zmax, a.inv_t);
+            const uint64_t mine = q[0] + q[1] + q[2] + q[3];
+            uint64_t incl = mine;  // inclusive prefix over lanes
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            q[e] = (i0 + e < V) ? weight_u64(z[i0 + e], zmax, a.inv_t) : 0ull;
-            mine += q[e];
-        }
-        // exclusive prefix over lanes
-        uint64_t incl = mine;
+            for (int o = 1; o < 64; o <<= 1) {
+                const uint32_t lo = __shfl_up((uint32_t)incl, o, kWave);
+                const uint32_t hi = __shfl_up((uint32_t)(incl >> 32), o, kWave);
+                if (lane >= o) incl += ((uint64_t)hi << 32) | lo;
+            }
+            const uint32_t blo = __shfl((uint32_t)incl, 63, kWave), bhi = __shfl((uint32_t)(incl >> 32), 63, kWave);
+            const uint64_t block_total = ((uint64_t)bhi << 32) | blo;
+            if (rem >= block_total) {  // uniform across the wave
+                rem -= block_total;
+                continue;
+            }
+            const uint64_t excl = incl - mine;
+            if (excl <= rem && rem < incl) {  // exactly one lane
+                uint64_t run = excl;
+                int tok = i0;
 #pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const uint32_t lo = __shfl_up((uint32_t)incl, o, kWave);
-            const uint32_t hi = __shfl_up((uint32_t)(incl >> 32), o, kWave);
-            if (lane >= o) incl += ((uint64_t)hi << 32) | lo;
-        }
-        const uint64_t excl = incl - mine;
-        // exactly one lane has excl <= rem < incl
-        if (excl <= rem && rem < incl) {
-            uint64_t run = excl;
-            int tok = i0;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                if (run + q[e] > rem) {
-                    tok = i0 + e;
-                    break;
+                for (int e = 0; e < 4; ++e) {
+                    if (run + q[e] > rem) {
+                        tok = i0 + e;
+                        break;
+                    }
+                    run += q[e];
                 }
-                run += q[e];
+                a.tokens_out[r] = tok;
+                if (a.logprob_out) {
+                    const float x = ((z[tok] - zmax) * a.inv_t);
+                    a.logprob_out[r] = x - (float)(log((double)row_total) - 40.0 * 0.6931471805599453);
+                }
             }
-            a.tokens_out[r] = tok;
-            if (a.logprob_out) {
-                // accumulate the same way as pass 2 would in floating point: log(q_total) via fp64
-                uint64_t total = 0;
-                for (int s2 = 0; s2 < n_seg; ++s2) total += seg_sum[s2];
-                const float x = ((z[tok] - zmax) * a.inv_t);
-                a.logprob_out[r] = x - (float)(log((double)total) - 40.0 * 0.6931471805599453);
-            }
+            break;
         }
     }
 }
@@ -182,14 +223,22 @@ __global__ __launch_bounds__(256) void lse_gather_kernel(const float* __restrict
     __shared__ float red2[4];
     const int r = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float* z = logits + (int64_t)r * row_stride;
+    const bool vec = ((uintptr_t)z % 16) == 0;
     float mx = -INFINITY;
-    for (int i = tid; i < vocab; i += 256) mx = fmaxf(mx, z[i]);
+    for (int i = tid * 4; i < vocab; i += 1024) {
+        const float4 v = load4(z, i, vocab, vec);
+        mx = fmaxf(fmaxf(mx, fmaxf(v.x, v.y)), fmaxf(v.z, v.w));
+    }
     mx = wave_max(mx);
     if (lane == 0) red[wave] = mx;
     __syncthreads();
     mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    const float k2 = inv_t * 1.4426950408889634f;  // exp(y) = 2^(y * log2 e)
     float sum = 0.f;
-    for (int i = tid; i < vocab; i += 256) sum += expf((z[i] - mx) * inv_t);
+    for (int i = tid * 4; i < vocab; i += 1024) {
+        const float4 v = load4(z, i, vocab, vec);  // -inf padding contributes 2^-inf = 0
+        sum += (exp2f((v.x - mx) * k2) + exp2f((v.y - mx) * k2)) + (exp2f((v.z - mx) * k2) + exp2f((v.w - mx) * k2));
+    }
     sum = wave_sum(sum);
     if (lane == 0) red2[wave] = sum;
     __syncthreads();
