@@ -22,8 +22,36 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK = {"hbm": (8000.0, "GB/s"), "mfma": (2500.0, "TFLOP/s")}
+# HBM-side bytes per launch of the dominant kernel's heaviest launch (prefill gate/up projection,
+# M=16384, N=17920, K=1536, SwiGLU epilogue), from two rocprofv3 --pmc runs (FETCH_SIZE x 2.0 and
+# WRITE_SIZE x 1.0 after calibration against a 1 GiB copy): profiles/gemm_hbm_traffic_pmc.txt.
+GEMM256_TRAFFIC = dict(launch="prefill gate/up projection M=16384 N=17920 K=1536", read_bytes=1340.4e6,
+                       write_bytes=293.6e6, algorithmic_bytes=105.4e6 + 293.6e6)
 KERNEL_BOUND = {"gemm256": "mfma", "gemm256x128": "mfma", "gemm128": "mfma", "gemm64": "mfma",
                 "attn_decode": "hbm", "sample": "hbm"}
+
+
+def algorithmic_decode_bytes(st) -> float:
+    """HBM bytes the decode loop must move (SURVEY 8(d) accounting): per step the layer and
+    LM-head weights once, the shared prefix KV once per live GROUP, each live rollout's private
+    KV, the new token's KV write, and the logits written by the LM head and read by the sampler."""
+    cfg = st["cfg"]
+    mc = cfg.model
+    es = 2 if mc.dtype == "bf16" else 4
+    per_layer = (mc.qkv_rows * mc.d_model + mc.d_model * mc.n_q_heads * mc.head_dim +
+                 2 * mc.d_ffn * mc.d_model + mc.d_model * mc.d_ffn)
+    w_bytes = (per_layer * mc.n_layers + mc.vocab * mc.d_model) * es
+    kv_tok = 2 * mc.n_kv_heads * mc.head_dim * es * mc.n_layers
+    m, G = st["m"], st["G"]
+    total = 0.0
+    for j in range(1, int(m.max())):
+        live = m > j
+        n_live = int(live.sum())
+        if n_live == 0:
+            break
+        prefix = sum(cfg.prompt_len + cfg.traj_len - int(mk) for mk in m[live])
+        total += w_bytes + prefix * kv_tok + n_live * G * (j + 1) * kv_tok + n_live * G * mc.vocab * 4 * 2
+    return total
 
 
 def build_case(workload: str, n_groups: int | None, max_rows: int):
@@ -57,15 +85,83 @@ def build_case(workload: str, n_groups: int | None, max_rows: int):
     return state
 
 
-def one_step(st, seed: int):
+def one_step(st, seed: int, marks=None):
+    import torch
     from paper_2601_19404_amd import binding as rpo
     from paper_2601_19404_amd import rollout
     res = rollout.suffix_rollout(st["batch"], st["prompts"], st["cached"], st["m"], st["cfg"].temperature,
-                                 seed, st["seq_ids"])
+                                 seed, st["seq_ids"], marks=marks)
     packed, cu_s = rollout.pack_suffixes(res.tokens, st["m"], st["G"], st["idx_dev"])
     rpo.rpo_suffix_logprobs(st["batch"], packed, cu_s, st["cfg"].temperature, st["lp_out"])
     rpo.grpo_advantages(st["rewards_dev"], st["ng"], st["G"], 0, 0.0, st["adv_out"])
+    if marks is not None:
+        ev = torch.cuda.Event(enable_timing=True)
+        ev.record()
+        marks.append(("logprobs+advantages", ev))
     return res
+
+
+def run_c4(args):
+    """Config C4: teacher-forced log-prob + advantage pass at the 7B shape, every sequence
+    re-prefilled on its own (a G = 1 batch: no prefix sharing), LM head on the suffix rows only."""
+    import torch
+    from paper_2601_19404_amd import binding as rpo
+    from paper_2601_19404_amd import synth
+    cfg = synth.CONFIGS["C4"]
+    mc = cfg.model
+    w = synth.make_weights(mc, seed=1234, device="cuda")
+    model = rpo.rpo_model_create(mc, w)
+    ng = cfg.n_groups if args.groups is None else args.groups
+    G, T = cfg.G, cfg.traj_len
+    wl = synth.make_workload(cfg, n_groups=ng)
+    n_seq = ng * G
+    rt = np.random.Generator(np.random.PCG64(1))
+    toks = rt.integers(0, mc.vocab, size=(n_seq, T), dtype=np.int32)
+    m_seq = np.repeat(wl.m, G)
+    order = np.argsort(-m_seq, kind="stable")
+    toks, m_seq = toks[order], m_seq[order]
+    pre = np.concatenate([toks[i, :T - m_seq[i]] for i in range(n_seq)])
+    suf = np.concatenate([toks[i, T - m_seq[i]:] for i in range(n_seq)])
+    cu_p = np.concatenate([[0], np.cumsum(T - m_seq)]).astype(np.int32)
+    cu_s = np.concatenate([[0], np.cumsum(m_seq)]).astype(np.int32)
+    max_prefix, max_suffix = int((T - m_seq).max()), int(m_seq.max())
+    batch = rpo.rpo_batch_create(model, n_seq, 1, max_prefix, max_suffix, 64, max(args.max_rows, max_prefix))
+    pre_d, suf_d = torch.from_numpy(pre).cuda(), torch.from_numpy(suf).cuda()
+    last = torch.empty(n_seq, mc.vocab, dtype=torch.float32, device="cuda")
+    lp = torch.empty(int(cu_s[-1]), dtype=torch.float32, device="cuda")
+    rewards = torch.from_numpy(wl.rewards).cuda()
+    adv = torch.empty(ng, G, dtype=torch.float32, device="cuda")
+
+    def step():
+        rpo.rpo_prefill_prefix(batch, pre_d, cu_p, last)
+        rpo.rpo_kv_fork(batch)
+        rpo.rpo_suffix_logprobs(batch, suf_d, cu_s, cfg.temperature, lp)
+        rpo.grpo_advantages(rewards, ng, G, 0, 0.0, adv)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / args.steps
+    per_layer = (mc.qkv_rows * mc.d_model + mc.d_model * mc.n_q_heads * mc.head_dim +
+                 3 * mc.d_ffn * mc.d_model)
+    rows = n_seq * T - n_seq            # the last token of a sequence is never pushed through the layers
+    flops = (2.0 * per_layer * mc.n_layers * rows
+             + 4.0 * mc.head_dim * mc.n_q_heads * mc.n_layers * n_seq * T * T / 2
+             + 2.0 * mc.vocab * mc.d_model * float(cu_s[-1]))
+    out = dict(metric="teacher-forced suffix log-prob + advantage pass, sequence tokens/sec at the 7B shape",
+               value=n_seq * T / dt, unit="tokens/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
+               ms_per_step=dt * 1e3, higher_is_better=True, scaling="weak", vs_baseline=None, dtype=mc.dtype,
+               data="synthetic",
+               config=dict(workload=cfg.name, model_shape=mc.name, sequences=n_seq, seq_len=T,
+                           suffix_tokens_scored=int(cu_s[-1]), mode="full re-prefill (G = 1 batch)"),
+               roofline=dict(bound="mfma", achieved=flops / dt / 1e12, peak=2500.0, unit="TFLOP/s",
+                             frac=flops / dt / 1e12 / 2500.0, traffic=None, kernel="whole pass",
+                             counted_PFLOP=flops / 1e15))
+    print(json.dumps(out), flush=True)
 
 
 def cpu_baseline(st, budget_tokens: int = 6, prefix_cap: int = 256, n_rollouts: int = 3):
@@ -107,12 +203,18 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="C1", choices=["C0", "C1", "C2", "C3"])
+    ap.add_argument("--workload", default="C1", choices=["C0", "C1", "C2", "C3", "C4"])
     ap.add_argument("--groups", type=int, default=None, help="override the number of groups (debugging)")
     ap.add_argument("--max-rows", type=int, default=16384)
     ap.add_argument("--profile-kernel", default="gemm256",
                     help="kernel whose launches are timed with HIP events for the roofline object")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--gemm-probe", default=None, metavar="M,N,K,EPI",
+                    help="only run the MFMA GEMM five times on one shape (bf16, N(0,1) inputs; EPI as in "
+                         "rpo_gemm_nt) so that rocprofv3 --pmc can read its HBM traffic, and exit")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="only copy 1 GiB device to device three times (calibrates the FETCH_SIZE / "
+                         "WRITE_SIZE counters of a rocprofv3 --pmc run) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1",
@@ -125,6 +227,29 @@ def main():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
     rpo.lib()
+    if args.copy_probe:
+        a = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes_each_way": a.numel() * 4}))
+        return
+    if args.gemm_probe:
+        M, N, K, epi = (int(v) for v in args.gemm_probe.split(","))
+        a = torch.randn(M, K, device="cuda").to(torch.bfloat16)
+        w = (torch.randn(N, K, device="cuda") * 0.02).to(torch.bfloat16)
+        c = torch.zeros(M, N // 2 if epi == 3 else N, device="cuda",
+                        dtype=torch.bfloat16 if epi in (0, 3) else torch.float32)
+        ws = torch.empty(96 << 20, dtype=torch.uint8, device="cuda")
+        for _ in range(5):
+            rpo.rpo_gemm_nt(a, w, c, epi, ws)
+        torch.cuda.synchronize()
+        print(json.dumps({"gemm_probe": [M, N, K, epi]}))
+        return
+    if args.workload == "C4":
+        run_c4(args)
+        return
     st = build_case(args.workload, args.groups, args.max_rows)
     cfg = st["cfg"]
     for i in range(args.warmup):
@@ -134,10 +259,17 @@ def main():
     kid = rpo.KERNEL_IDS[args.profile_kernel]
     rpo.rpo_profile_start(kid)
     t0 = time.perf_counter()
+    all_marks = []
     for i in range(args.steps):
-        res = one_step(st, seed=200 + i)
+        marks = []
+        res = one_step(st, seed=200 + i, marks=marks)
+        all_marks.append(marks)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    phases = {}
+    for marks in all_marks:
+        for (_, e0), (name, e1) in zip(marks[:-1], marks[1:]):
+            phases[name] = phases.get(name, 0.0) + e0.elapsed_time(e1) / args.steps
     launches, k_ms, k_flops, k_bytes = rpo.rpo_profile_stop()
 
     n_gen = res.n_generated
@@ -149,7 +281,11 @@ def main():
         achieved = work / (k_ms / 1e3)
     else:
         achieved = 0.0
-    roofline = dict(bound=bound, achieved=achieved, peak=peak, unit=unit, frac=achieved / peak, traffic=None,
+    traffic = None
+    if args.profile_kernel == "gemm256" and args.workload == "C1":
+        traffic = GEMM256_TRAFFIC["read_bytes"] + GEMM256_TRAFFIC["write_bytes"]
+    roofline = dict(bound=bound, achieved=achieved, peak=peak, unit=unit, frac=achieved / peak, traffic=traffic,
+                    traffic_of=GEMM256_TRAFFIC if traffic else None,
                     kernel=args.profile_kernel, launches=launches,
                     avg_launch_us=(k_ms * 1e3 / launches) if launches else None,
                     share_of_step_time=(k_ms / 1e3) / dt)
@@ -162,6 +298,12 @@ def main():
                            suffix_len_range=[int(st["m"].min()), int(st["m"].max())],
                            generated_tokens_per_step=int(n_gen), page_tokens=st["page"],
                            temperature=cfg.temperature),
+               phase_ms_per_step={k: round(v, 2) for k, v in phases.items()},
+               decode_tokens_per_s=(n_gen - st["ng"] * st["G"]) / (phases.get("decode", float("nan")) / 1e3),
+               decode_hbm=dict(algorithmic_GB_per_step=round(algorithmic_decode_bytes(st) / 1e9, 2),
+                               achieved_GBps=algorithmic_decode_bytes(st) / 1e9 / (phases.get("decode", float("nan")) / 1e3),
+                               peak_GBps=8000.0,
+                               frac=algorithmic_decode_bytes(st) / 1e9 / (phases.get("decode", float("nan")) / 1e3) / 8000.0),
                roofline=roofline)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(st)

@@ -485,6 +485,41 @@ __global__ __launch_bounds__(256) void gemm_splitk_reduce_kernel(const float* __
         ((float*)Cv)[o] += v;
 }
 
+// K-split reduction fused with the residual add and the following RMSNorm: one workgroup per
+// row; x[m, :] += sum_z P[z][m, :], then h[m, :] = x / sqrt(mean(x^2) + eps) * gain.
+__global__ __launch_bounds__(256) void gemm_splitk_reduce_norm_kernel(const float* __restrict__ P, int splits,
+                                                                      int M, int N, float* __restrict__ X,
+                                                                      int64_t ldc, const bf16* __restrict__ gain,
+                                                                      float eps, bf16* __restrict__ H) {
+    constexpr int kMaxPer = 32;  // N <= 8192
+    __shared__ float part[4];
+    const int m = blockIdx.x, tid = threadIdx.x;
+    const int64_t plane = (int64_t)M * N;
+    float v[kMaxPer];
+    float ss = 0.f;
+#pragma unroll
+    for (int i = 0; i < kMaxPer; ++i) {
+        const int c = tid + i * 256;
+        if (c < N) {
+            float acc = X[(int64_t)m * ldc + c];
+            for (int z = 0; z < splits; ++z) acc += P[z * plane + (int64_t)m * N + c];
+            X[(int64_t)m * ldc + c] = acc;
+            v[i] = acc;
+            ss += acc * acc;
+        }
+    }
+    ss = wave_sum(ss);
+    if ((tid & 63) == 0) part[tid >> 6] = ss;
+    __syncthreads();
+    const float tot = (part[0] + part[1]) + (part[2] + part[3]);
+    const float inv = 1.0f / sqrtf(tot / (float)N + eps);
+#pragma unroll
+    for (int i = 0; i < kMaxPer; ++i) {
+        const int c = tid + i * 256;
+        if (c < N) H[(int64_t)m * N + c] = f32_to_bf16(v[i] * inv * bf16_to_f32(gain[c]));
+    }
+}
+
 // ---------------------------------------------------------------------------
 // launch logic
 // ---------------------------------------------------------------------------
@@ -590,6 +625,12 @@ hipError_t launch_tile(const GemmArgs& a, int splits, hipStream_t s) {
                 gemm_splitk_reduce_kernel<kEpiStoreF32><<<blocks, 256, 0, s>>>(P, splits, a.M, a.N, a.C, a.ldc);
                 break;
             case kEpiAddF32:
+                if (a.norm_out && a.N <= 8192) {
+                    gemm_splitk_reduce_norm_kernel<<<a.M, 256, 0, s>>>(P, splits, a.M, a.N, (float*)a.C, a.ldc,
+                                                                        (const bf16*)a.norm_gain, a.norm_eps,
+                                                                        (bf16*)a.norm_out);
+                    return hipGetLastError();
+                }
                 gemm_splitk_reduce_kernel<kEpiAddF32><<<blocks, 256, 0, s>>>(P, splits, a.M, a.N, a.C, a.ldc);
                 break;
             default:
@@ -647,11 +688,7 @@ int gemm_kernel_id(const GemmArgs& a) {
     return pick_tile(a).id;
 }
 
-hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
-    if (a.M <= 0 || a.N <= 0) return hipSuccess;
-    if (!mfma_ok(a)) return a.dtype == kF32 ? launch_generic<float>(a, s) : launch_generic<bf16>(a, s);
-    const TileCfg t = pick_tile(a);
-    const int splits = (a.ws && a.ws_bytes) ? pick_splits(a, t) : 1;
+static hipError_t launch_gemm_only(const GemmArgs& a, int splits, const TileCfg& t, hipStream_t s) {
     switch (t.id) {
         case kKidGemm256:
             return launch_tile<256, 256, 2, 4>(a, splits, s);
@@ -662,6 +699,23 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
         default:
             return launch_tile<64, 128, 1, 2>(a, splits, s);
     }
+}
+
+hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
+    if (a.M <= 0 || a.N <= 0) return hipSuccess;
+    const bool want_norm = a.norm_out != nullptr && a.epilogue == kEpiAddF32;
+    hipError_t e;
+    bool norm_done = false;
+    if (!mfma_ok(a)) {
+        e = a.dtype == kF32 ? launch_generic<float>(a, s) : launch_generic<bf16>(a, s);
+    } else {
+        const TileCfg t = pick_tile(a);
+        const int splits = (a.ws && a.ws_bytes) ? pick_splits(a, t) : 1;
+        e = launch_gemm_only(a, splits, t, s);
+        norm_done = want_norm && splits > 1 && a.N <= 8192;  // fused into the K-split reduction
+    }
+    if (e != hipSuccess || !want_norm || norm_done) return e;
+    return launch_rmsnorm((const float*)a.C, nullptr, a.norm_gain, a.dtype, a.N, a.norm_eps, a.norm_out, a.M, s);
 }
 
 }  // namespace rpo

@@ -39,6 +39,12 @@ struct GemmArgs {
     int path;      // 0 = pick, 1 = force the generic (non-MFMA) kernel
     void* ws;      // fp32 scratch for K-split partial sums (may be null: no splitting)
     size_t ws_bytes;
+    // Optional, with kEpiAddF32 only: after C += A W^T, also write the RMS-normalised rows
+    // norm_out[m, :] = C[m, :] / sqrt(mean(C[m, :]^2) + norm_eps) * norm_gain (input dtype, row
+    // stride N).  Fused into the K-split reduction when the problem is split.
+    const void* norm_gain = nullptr;
+    void* norm_out = nullptr;
+    float norm_eps = 0.f;
 };
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
 

@@ -372,6 +372,7 @@ struct PassCfg {
     int max_shared_pages;
     double attn_flops = 0.0;  // algorithmic work of ONE layer's attention launch (for timing reports)
     double attn_bytes = 0.0;
+    void* final_norm_out = nullptr;  // if set: final RMSNorm of all rows is written here by the last layer
 };
 
 #define RET_IF(expr)                       \
@@ -381,7 +382,8 @@ struct PassCfg {
     } while (0)
 
 hipError_t gemm(rpo_batch* b, const void* A, int64_t lda, const void* W, int64_t ldw, void* C,
-                int64_t ldc, int M, int N, int K, int epi, hipStream_t s) {
+                int64_t ldc, int M, int N, int K, int epi, hipStream_t s, const void* norm_gain = nullptr,
+                void* norm_out = nullptr) {
     const rpo_model* m = b->m;
     GemmArgs g;
     g.A = A;
@@ -398,6 +400,9 @@ hipError_t gemm(rpo_batch* b, const void* A, int64_t lda, const void* W, int64_t
     g.path = g_kernel_path;
     g.ws = b->at<void>(b->L.gu);
     g.ws_bytes = kSplitKBytes;
+    g.norm_gain = norm_gain;
+    g.norm_out = norm_out;
+    g.norm_eps = m->d.rms_eps;
     const double es = (double)dtype_size(g.dtype);
     const double out_bytes = epi == kEpiStore ? (double)M * N * es
                              : epi == kEpiStoreF32 ? (double)M * N * 4.0
@@ -418,8 +423,10 @@ hipError_t run_layers(rpo_batch* b, const PassCfg& pc, hipStream_t s) {
     void* act = b->at<void>(L.act);
     const int qw = m->qkv_width();
     const int qd = d.n_q_heads * d.head_dim;
+    // Every RMSNorm but the first rides on the projection that produces its input (the
+    // residual-adding O and down GEMMs write the normalised rows too).
+    RET_IF(launch_rmsnorm(x, nullptr, m->attn_norm[0], d.dtype, d.d_model, d.rms_eps, h, pc.rows, s));
     for (int l = 0; l < d.n_layers; ++l) {
-        RET_IF(launch_rmsnorm(x, nullptr, m->attn_norm[l], d.dtype, d.d_model, d.rms_eps, h, pc.rows, s));
         RET_IF(gemm(b, h, d.d_model, m->wqkv[l], d.d_model, qkv, qw, pc.rows, qw, d.d_model, kEpiStore, s));
         RopeKvArgs ra;
         ra.qkv = qkv;
@@ -474,12 +481,15 @@ hipError_t run_layers(rpo_batch* b, const PassCfg& pc, hipStream_t s) {
             RET_IF(timed(attn_uses_mfma(aa) ? kKidAttnChunk : 0, pc.attn_flops, pc.attn_bytes, s,
                          [&] { return launch_attn_chunk(aa, s); }));
         }
-        RET_IF(gemm(b, attn, qd, m->wo[l], qd, x, d.d_model, pc.rows, d.d_model, qd, kEpiAddF32, s));
-        RET_IF(launch_rmsnorm(x, nullptr, m->ffn_norm[l], d.dtype, d.d_model, d.rms_eps, h, pc.rows, s));
+        RET_IF(gemm(b, attn, qd, m->wo[l], qd, x, d.d_model, pc.rows, d.d_model, qd, kEpiAddF32, s,
+                    m->ffn_norm[l], h));
         RET_IF(gemm(b, h, d.d_model, m->w_gate_up[l], d.d_model, act, d.d_ffn, pc.rows, 2 * d.d_ffn, d.d_model,
                     kEpiSwiglu, s));
+        const bool last = l + 1 == d.n_layers;
+        const void* next_gain = last ? (pc.final_norm_out ? m->final_norm : nullptr) : m->attn_norm[l + 1];
+        void* next_out = last ? pc.final_norm_out : h;
         RET_IF(gemm(b, act, d.d_ffn, m->w_down[l], d.d_ffn, x, d.d_model, pc.rows, d.d_model, d.d_ffn,
-                    kEpiAddF32, s));
+                    kEpiAddF32, s, next_gain, next_gain ? next_out : nullptr));
     }
     return hipSuccess;
 }
@@ -651,8 +661,10 @@ extern "C" int rpo_decode_step(rpo_batch* b, const int32_t* tokens_dev, int32_t 
         pc.attn_bytes = toks * tok_bytes;
         pc.attn_flops = 4.0 * qk * d.n_q_heads * d.head_dim;
     }
+    pc.final_norm_out = b->at<void>(L.hl);
     HIP_TRY(run_layers(b, pc, s));
-    HIP_TRY(lm_head_rows(b, nullptr, n_rows, logits_dev, s));
+    HIP_TRY(gemm(b, b->at<void>(L.hl), d.d_model, b->m->lm_head, d.d_model, logits_dev, d.vocab, n_rows, d.vocab,
+                 d.d_model, kEpiStoreF32, s));
     b->step += 1;
     return RPO_OK;
 }

@@ -42,13 +42,15 @@ class RolloutResult:
 
 
 def suffix_rollout(batch: rpo.Batch, prompts, cached, m, temperature: float, seed: int,
-                   seq_ids: torch.Tensor, keep_logits: bool | int = False, stream=None) -> RolloutResult:
+                   seq_ids: torch.Tensor, keep_logits: bool | int = False, stream=None,
+                   marks: list | None = None) -> RolloutResult:
     """Regenerate m_k tokens for each of the G rollouts of every group.
 
     Groups must be ordered by decreasing m (see order_by_suffix_length) so that the
     live rows are always a leading block.  seq_ids: uint64-valued int64 device tensor
     [B], the Philox stream id of each rollout row.  keep_logits: True keeps a copy of every
-    step's logits (tests), an integer n only those of the first n steps."""
+    step's logits (tests), an integer n only those of the first n steps.  marks: if a list,
+    (name, torch.cuda.Event) pairs are appended at the phase boundaries (benchmark timing)."""
     cfg = batch.model.cfg
     G, ng = batch.G, batch.n_groups
     B = ng * G
@@ -67,8 +69,16 @@ def suffix_rollout(batch: rpo.Batch, prompts, cached, m, temperature: float, see
     kept = [] if keep_logits else None
     n_keep = max_m if keep_logits is True else int(keep_logits)
 
+    def mark(name):
+        if marks is not None:
+            ev = torch.cuda.Event(enable_timing=True)
+            ev.record(stream)
+            marks.append((name, ev))
+
+    mark("start")
     rpo.rpo_prefill_prefix(batch, tokens_dev, cu, last_logits, stream)
     rpo.rpo_kv_fork(batch, stream)
+    mark("prefill+fork")
     # rows alive at step j: groups with m > j, a leading block because m is non-increasing
     live_groups = [int(np.sum(m > j)) for j in range(max_m)]
     if max_m > 0:
@@ -86,6 +96,7 @@ def suffix_rollout(batch: rpo.Batch, prompts, cached, m, temperature: float, see
                        out_lp[j], stream)
         if j < n_keep:
             kept.append(logits[:n].clone())
+    mark("decode")
     return RolloutResult(out_tokens.t().contiguous(), out_lp.t().contiguous(), m, cu,
                          int(m.sum()) * G, kept)
 
