@@ -182,6 +182,17 @@ int rpo_suffix_logprobs(rpo_batch *b, const int32_t *suffix_tokens_dev, const in
 int grpo_advantages(const float *rewards_dev, int32_t n_groups, int32_t G, int32_t ddof, float eps,
                     float *adv_out_dev, void *stream);
 
+/* Length-aware reward shaping, Eq. 11 (Sec. 3.4): R_i = clip(r_i / (1 + exp(-alpha (l_ref - len_i))),
+ * lo, hi) with l_ref the mean response length of the group; the paper uses lo 0.5, hi 1,
+ * alpha 0.01 (Sec. 4.1).  Reading: applied to positive rewards only, r_i <= 0 gives R_i = 0
+ * (literally, a wrong answer would be lifted to `lo`).  fp64 arithmetic, result fp32; feed
+ * the result to grpo_advantages.
+ *   rewards_dev device fp32 [n_groups, G]; lengths_dev device int32 [n_groups, G] (tokens per
+ *   response); shaped_out_dev device fp32 [n_groups, G].
+ * Errors: RPO_EINVAL (NULL, G < 1, alpha <= 0, lo > hi). */
+int rpo_shape_rewards(const float *rewards_dev, const int32_t *lengths_dev, int32_t n_groups, int32_t G,
+                      float alpha, float lo, float hi, float *shaped_out_dev, void *stream);
+
 /* Thread-local message of the last failing call in this thread ("" if none). */
 const char *rpo_last_error(void);
 

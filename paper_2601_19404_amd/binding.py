@@ -70,6 +70,7 @@ def lib() -> C.CDLL:
     L.rpo_sample.argtypes = [vp, i32, i32, i64, vp, i32, f32, u64, vp, u32, vp, vp, vp]
     L.rpo_suffix_logprobs.argtypes = [vp, vp, C.POINTER(i32), f32, vp, vp]
     L.grpo_advantages.argtypes = [vp, i32, i32, i32, f32, vp, vp]
+    L.rpo_shape_rewards.argtypes = [vp, vp, i32, i32, f32, f32, f32, vp, vp]
     L.rpo_gemm_nt.argtypes = [vp, i64, vp, i64, vp, i64, i32, i32, i32, i32, i32, vp, sz, vp]
     L.rpo_set_kernel_path.argtypes = [C.c_int]
     L.rpo_profile_start.argtypes = [C.c_int]
@@ -77,7 +78,7 @@ def lib() -> C.CDLL:
                                    C.POINTER(C.c_double)]
     for name in ("rpo_model_create", "rpo_batch_create", "rpo_prefill_prefix", "rpo_kv_fork",
                  "rpo_decode_step", "rpo_sample", "rpo_suffix_logprobs", "grpo_advantages",
-                 "rpo_gemm_nt", "rpo_set_kernel_path", "rpo_profile_start", "rpo_profile_stop"):
+                 "rpo_shape_rewards", "rpo_gemm_nt", "rpo_set_kernel_path", "rpo_profile_start", "rpo_profile_stop"):
         getattr(L, name).restype = C.c_int
     _lib = L
     return L
@@ -86,7 +87,7 @@ def lib() -> C.CDLL:
 EXPORTS = ("rpo_model_create", "rpo_model_destroy", "rpo_kv_pool_bytes", "rpo_workspace_bytes",
            "rpo_batch_create", "rpo_batch_destroy", "rpo_prefill_prefix", "rpo_kv_fork",
            "rpo_decode_step", "rpo_sample", "rpo_suffix_logprobs", "grpo_advantages",
-           "rpo_last_error", "rpo_gemm_nt", "rpo_set_kernel_path", "rpo_profile_start",
+           "rpo_shape_rewards", "rpo_last_error", "rpo_gemm_nt", "rpo_set_kernel_path", "rpo_profile_start",
            "rpo_profile_stop")
 
 
@@ -260,6 +261,17 @@ def grpo_advantages(rewards_dev: torch.Tensor, n_groups: int, G: int, ddof: int,
         raise ValueError("rewards / advantages smaller than n_groups x G")
     _check(lib().grpo_advantages(rewards_dev.data_ptr(), n_groups, G, ddof, eps, adv_out_dev.data_ptr(),
                                  _stream(stream)))
+
+
+def rpo_shape_rewards(rewards_dev: torch.Tensor, lengths_dev: torch.Tensor, n_groups: int, G: int,
+                      alpha: float, lo: float, hi: float, shaped_out_dev: torch.Tensor, stream=None) -> None:
+    _dev(rewards_dev, torch.float32, "rewards_dev")
+    _dev(lengths_dev, torch.int32, "lengths_dev")
+    _dev(shaped_out_dev, torch.float32, "shaped_out_dev")
+    if min(rewards_dev.numel(), lengths_dev.numel(), shaped_out_dev.numel()) < n_groups * G:
+        raise ValueError("buffers smaller than n_groups x G")
+    _check(lib().rpo_shape_rewards(rewards_dev.data_ptr(), lengths_dev.data_ptr(), n_groups, G, alpha, lo, hi,
+                                   shaped_out_dev.data_ptr(), _stream(stream)))
 
 
 def rpo_gemm_nt(a_dev: torch.Tensor, w_dev: torch.Tensor, c_dev: torch.Tensor, epilogue: int,

@@ -795,6 +795,16 @@ extern "C" int grpo_advantages(const float* rewards_dev, int32_t n_groups, int32
     return RPO_OK;
 }
 
+extern "C" int rpo_shape_rewards(const float* rewards_dev, const int32_t* lengths_dev, int32_t n_groups, int32_t G,
+                                 float alpha, float lo, float hi, float* shaped_out_dev, void* stream) {
+    if (!rewards_dev || !lengths_dev || !shaped_out_dev) return fail(RPO_EINVAL, "rpo_shape_rewards: NULL argument");
+    if (n_groups < 0 || G < 1) return fail(RPO_EINVAL, "rpo_shape_rewards: bad sizes");
+    if (!(alpha > 0.f) || !(lo <= hi)) return fail(RPO_EINVAL, "rpo_shape_rewards: need alpha > 0 and lo <= hi");
+    HIP_TRY(launch_shape_rewards(rewards_dev, lengths_dev, n_groups, G, alpha, lo, hi, shaped_out_dev,
+                                 (hipStream_t)stream));
+    return RPO_OK;
+}
+
 // ---------------------------------------------------------------------------
 extern "C" int rpo_gemm_nt(const void* a_dev, int64_t lda, const void* w_dev, int64_t ldw, void* c_dev,
                            int64_t ldc, int32_t M, int32_t N, int32_t K, int32_t dtype, int32_t epilogue,

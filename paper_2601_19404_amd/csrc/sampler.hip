@@ -286,6 +286,38 @@ __global__ __launch_bounds__(64) void advantages_kernel(const float* __restrict_
     for (int i = 0; i < G; ++i) o[i] = (float)(((double)r[i] - mu) / den);
 }
 
+// Eq. 11 of the paper: R = clip(r / (1 + exp(-alpha (l_ref - len))), lo, hi) for r > 0, else 0;
+// l_ref = mean response length of the group.  One thread per group, fp64.
+__global__ __launch_bounds__(64) void shape_rewards_kernel(const float* __restrict__ rewards,
+                                                           const int32_t* __restrict__ lengths, int n_groups,
+                                                           int G, float alpha, float lo, float hi,
+                                                           float* __restrict__ out) {
+    const int k = blockIdx.x * 64 + threadIdx.x;
+    if (k >= n_groups) return;
+    const float* r = rewards + (int64_t)k * G;
+    const int32_t* ln = lengths + (int64_t)k * G;
+    float* o = out + (int64_t)k * G;
+    double s = 0.0;
+    for (int i = 0; i < G; ++i) s += (double)ln[i];
+    const double l_ref = s / (double)G;
+    for (int i = 0; i < G; ++i) {
+        const double raw = (double)r[i];
+        double v = 0.0;
+        if (raw > 0.0) {
+            const double w = 1.0 / (1.0 + exp(-(double)alpha * (l_ref - (double)ln[i])));
+            v = fmin(fmax(raw * w, (double)lo), (double)hi);
+        }
+        o[i] = (float)v;
+    }
+}
+
+hipError_t launch_shape_rewards(const float* rewards, const int32_t* lengths, int n_groups, int G, float alpha,
+                                float lo, float hi, float* out, hipStream_t s) {
+    if (n_groups <= 0) return hipSuccess;
+    shape_rewards_kernel<<<ceil_div(n_groups, 64), 64, 0, s>>>(rewards, lengths, n_groups, G, alpha, lo, hi, out);
+    return hipGetLastError();
+}
+
 hipError_t launch_advantages(const float* rewards, int n_groups, int G, int ddof, float eps, float* adv,
                              hipStream_t s) {
     if (n_groups <= 0) return hipSuccess;

@@ -188,3 +188,26 @@ def test_advantages_bit_exact(rpo):
         rpo.grpo_advantages(torch.zeros(2, 2, device="cuda"), 2, 2, 2, 0.0, torch.zeros(2, 2, device="cuda"))
     with pytest.raises(rpo.RpoError):
         rpo.grpo_advantages(torch.zeros(2, 1, device="cuda"), 2, 1, 1, 0.0, torch.zeros(2, 1, device="cuda"))
+
+
+def test_reward_shaping_then_advantages(rpo):
+    """Eq. 11 on the GPU against the oracle (fp64 exp from two libraries: 1e-6), then Eq. 7 on the
+    shaped rewards (bit-exact given the same inputs)."""
+    from oracle import reward_shaping as ors
+    rng = np.random.default_rng(4)
+    ng, g = 37, 8
+    r = (rng.random((ng, g)) < 0.6).astype(np.float32)
+    ln = rng.integers(50, 4096, size=(ng, g)).astype(np.int32)
+    out = torch.empty(ng, g, dtype=torch.float32, device="cuda")
+    for alpha, lo, hi in ((0.01, 0.5, 1.0), (0.002, 0.1, 0.9)):
+        rpo.rpo_shape_rewards(torch.from_numpy(r).cuda(), torch.from_numpy(ln).cuda(), ng, g, alpha, lo, hi, out)
+        torch.cuda.synchronize()
+        ref = ors.shape_rewards(r, ln, alpha, lo, hi)
+        got = out.cpu().numpy()
+        np.testing.assert_allclose(got, ref, atol=1e-6)
+        assert np.all(got[r == 0] == 0)
+        adv = torch.empty(ng, g, dtype=torch.float32, device="cuda")
+        rpo.grpo_advantages(out, ng, g, 0, 0.0, adv)
+        np.testing.assert_array_equal(adv.cpu().numpy(), oadv.grpo_advantages(got))
+    with pytest.raises(rpo.RpoError):
+        rpo.rpo_shape_rewards(out, torch.zeros(ng, g, dtype=torch.int32, device="cuda"), ng, g, 0.0, 0.5, 1.0, out)
