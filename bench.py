@@ -97,7 +97,7 @@ def one_step(st, seed: int, marks=None):
     if marks is not None:
         ev = torch.cuda.Event(enable_timing=True)
         ev.record()
-        marks.append(("logprobs+advantages", ev))
+        marks.append(("logprobs+advantages", ev, time.perf_counter()))
     return res
 
 
@@ -266,10 +266,11 @@ def main():
         all_marks.append(marks)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    phases = {}
+    phases, enqueue = {}, {}
     for marks in all_marks:
-        for (_, e0), (name, e1) in zip(marks[:-1], marks[1:]):
+        for (_, e0, c0), (name, e1, c1) in zip(marks[:-1], marks[1:]):
             phases[name] = phases.get(name, 0.0) + e0.elapsed_time(e1) / args.steps
+            enqueue[name] = enqueue.get(name, 0.0) + (c1 - c0) * 1e3 / args.steps
     launches, k_ms, k_flops, k_bytes = rpo.rpo_profile_stop()
 
     n_gen = res.n_generated
@@ -299,6 +300,7 @@ def main():
                            generated_tokens_per_step=int(n_gen), page_tokens=st["page"],
                            temperature=cfg.temperature),
                phase_ms_per_step={k: round(v, 2) for k, v in phases.items()},
+               host_enqueue_ms_per_step={k: round(v, 2) for k, v in enqueue.items()},
                decode_tokens_per_s=(n_gen - st["ng"] * st["G"]) / (phases.get("decode", float("nan")) / 1e3),
                decode_hbm=dict(algorithmic_GB_per_step=round(algorithmic_decode_bytes(st) / 1e9, 2),
                                achieved_GBps=algorithmic_decode_bytes(st) / 1e9 / (phases.get("decode", float("nan")) / 1e3),

@@ -391,14 +391,19 @@ static bool mfma_attn_ok(const AttnArgs& a) {
 
 bool attn_uses_mfma(const AttnArgs& a) { return mfma_attn_ok(a); }
 
-static hipError_t set_attn_lds(const void* fn) {
-    return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAttnLds);
+// Raise the dynamic-LDS limit of a kernel once per process (the call is a host round trip).
+static hipError_t set_attn_lds(const void* fn, bool* done) {
+    if (*done) return hipSuccess;
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAttnLds);
+    if (e == hipSuccess) *done = true;
+    return e;
 }
 
 hipError_t launch_attn_chunk(const AttnArgs& a, hipStream_t s) {
     if (a.rows <= 0 || a.n_seqs <= 0) return hipSuccess;
     if (!mfma_attn_ok(a)) return launch_attn_generic(a, s);
-    hipError_t e = set_attn_lds((const void*)attn_chunk_mfma_kernel);
+    static bool lds_set = false;
+    hipError_t e = set_attn_lds((const void*)attn_chunk_mfma_kernel, &lds_set);
     if (e != hipSuccess) return e;
     const int ntt = 64 / (a.Hq / a.Hkv);
     const dim3 grid(ceil_div(a.max_seq_rows, ntt), a.Hkv, a.n_seqs);
@@ -435,7 +440,8 @@ hipError_t launch_attn_decode(const DecodeAttnArgs& d, hipStream_t s) {
     if (n_slots * (kDh + 2) > d.partial_floats) return hipErrorInvalidValue;
     float* part_o = d.partial;
     float* part_ml = d.partial + n_slots * kDh;
-    hipError_t e = set_attn_lds((const void*)attn_decode_mfma_kernel);
+    static bool lds_set = false;
+    hipError_t e = set_attn_lds((const void*)attn_decode_mfma_kernel, &lds_set);
     if (e != hipSuccess) return e;
     const dim3 grid(dg.n_split * dg.n_ct + d.G, a.Hkv, n_groups_live);
     attn_decode_mfma_kernel<<<grid, 256, kAttnLds, s>>>(a, dg, d.shared_pages, part_o, part_ml);

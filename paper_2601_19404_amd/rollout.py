@@ -69,11 +69,13 @@ def suffix_rollout(batch: rpo.Batch, prompts, cached, m, temperature: float, see
     kept = [] if keep_logits else None
     n_keep = max_m if keep_logits is True else int(keep_logits)
 
+    import time
+
     def mark(name):
         if marks is not None:
             ev = torch.cuda.Event(enable_timing=True)
             ev.record(stream)
-            marks.append((name, ev))
+            marks.append((name, ev, time.perf_counter()))
 
     mark("start")
     rpo.rpo_prefill_prefix(batch, tokens_dev, cu, last_logits, stream)
