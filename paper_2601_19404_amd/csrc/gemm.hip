@@ -165,6 +165,12 @@ __device__ inline void gemm_epilogue(f32x16_t (&acc)[MI][NI], void* __restrict__
 constexpr int kBK = 64;
 constexpr int kLdsRow = kBK + 8;
 constexpr int kXcd = 8;  // XCDs of an MI355X; workgroup i is dispatched to XCD i % 8
+// Direct-to-LDS pipeline shape.  Measured on the prefill gate/up projection: 64-deep slabs in two
+// stages 907 TFLOP/s, 32-deep slabs in four stages 870, four waves of 128x128 833: not latency-bound.
+#ifndef RPO_DMA_BK
+#define RPO_DMA_BK 64
+#define RPO_DMA_STAGES 2
+#endif
 
 // Column n of the (virtual) output -> row of W.  SwiGLU mode interleaves gate and up rows
 // in blocks of 32: virtual columns [64q, 64q+32) are gate rows 32q.., [64q+32, 64q+64) up rows.
@@ -342,7 +348,16 @@ __device__ inline void dma_load16(const void* gptr, uint32_t lds_byte_addr) {
         : "memory");
 }
 
-template <int BM, int BN, int WM, int WN, int EPI, bool SWIGLU>
+// Position permutation of the 16-byte pieces of an LDS row (see above), for rows of 8 pieces
+// (64-deep slabs) and of 4 pieces (32-deep slabs).  Conflict-free for 16-byte reads of 16
+// consecutive rows whether the LDS serves 8 or 16 lanes per cycle.
+template <int BK>
+__device__ inline int lds_swizzle(int row) {
+    if (BK == 64) return (row & 7) ^ ((row >> 3) & 1);
+    return ((row >> 2) & 3) ^ (((row >> 1) & 1) << 1);
+}
+
+template <int BM, int BN, int WM, int WN, int EPI, bool SWIGLU, int BK, int STAGES>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const bf16* __restrict__ A, int64_t lda,
                                                                const bf16* __restrict__ W, int64_t ldw,
                                                                void* __restrict__ Cv, int64_t ldc, int M,
@@ -351,17 +366,21 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const bf16* __res
     constexpr int NW = WM * WN;
     constexpr int TM = BM / WM, TN = BN / WN;
     constexpr int MI = TM / 32, NI = TN / 32;
-    constexpr int A_INST = BM / 8 / NW;  // wave instructions per slab (8 rows each)
-    constexpr int B_INST = BN / 8 / NW;
-    constexpr int A_STAGE = BM * kBK, B_STAGE = BN * kBK;  // elements
-    static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile/wave mismatch");
+    constexpr int PIECES = BK / 8;             // 16-byte pieces per row
+    constexpr int ROWS_PER_INST = 64 / PIECES;  // rows one wave instruction fills (1 KiB)
+    constexpr int A_INST = BM / ROWS_PER_INST / NW;
+    constexpr int B_INST = BN / ROWS_PER_INST / NW;
+    constexpr int A_STAGE = BM * BK, B_STAGE = BN * BK;  // elements
+    static_assert(BK == 64 || BK == 32, "slab depth");
+    static_assert(BM % (ROWS_PER_INST * NW) == 0 && BN % (ROWS_PER_INST * NW) == 0, "tile/wave mismatch");
     static_assert(!SWIGLU || NI % 2 == 0, "SwiGLU needs gate/up block pairs inside a wave");
+    static_assert(STAGES >= 2 && STAGES <= 4, "pipeline depth");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    bf16* As = (bf16*)smem_raw;        // [2][BM][64]
-    bf16* Bs = As + 2 * A_STAGE;       // [2][BN][64]
+    bf16* As = (bf16*)smem_raw;             // [STAGES][BM][BK]
+    bf16* Bs = As + STAGES * A_STAGE;       // [STAGES][BN][BK]
     const uint32_t lds_a = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem_raw;
-    const uint32_t lds_b = lds_a + 2 * A_STAGE * 2;
+    const uint32_t lds_b = lds_a + STAGES * A_STAGE * 2;
 
     const int per_xcd = (n_tiles + kXcd - 1) / kXcd;
     const int logical = (blockIdx.x % kXcd) * per_xcd + blockIdx.x / kXcd;
@@ -379,33 +398,34 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const bf16* __res
     const int wm = wave % WM, wn = wave / WM;
     const int k_begin = blockIdx.y * k_per_split;
     const int k_end = min(K, k_begin + k_per_split);
-    const int nk = (k_end - k_begin) / kBK;
+    const int nk = (k_end - k_begin) / BK;
 
-    // Load addressing.  Instruction j of this wave fills row group rg = j * NW + wave
-    // (rows 8 rg .. 8 rg + 7); this lane's row is 8 rg + lane / 8 and it stores at position
-    // lane % 8, i.e. it fetches piece (lane % 8) ^ g(row).
+    // Load addressing.  Instruction j of this wave fills row group rg = j * NW + wave; this lane's
+    // row is rg * ROWS_PER_INST + lane / PIECES and it stores at position lane % PIECES, i.e. it
+    // fetches piece (lane % PIECES) ^ swizzle(row).
     const bf16* a_src[A_INST];
     const bf16* b_src[B_INST];
 #pragma unroll
     for (int j = 0; j < A_INST; ++j) {
-        const int rg = j * NW + wave;
-        const int row = rg * 8 + (lane >> 3);
-        const int piece = (lane & 7) ^ (lane >> 3) ^ (rg & 1);
+        const int row = (j * NW + wave) * ROWS_PER_INST + lane / PIECES;
+        const int piece = (lane % PIECES) ^ lds_swizzle<BK>(row);
         a_src[j] = A + (int64_t)min(m0 + row, M - 1) * lda + piece * 8 + k_begin;
     }
 #pragma unroll
     for (int j = 0; j < B_INST; ++j) {
-        const int rg = j * NW + wave;
-        const int row = rg * 8 + (lane >> 3);
-        const int piece = (lane & 7) ^ (lane >> 3) ^ (rg & 1);
+        const int row = (j * NW + wave) * ROWS_PER_INST + lane / PIECES;
+        const int piece = (lane % PIECES) ^ lds_swizzle<BK>(row);
         b_src[j] = W + (int64_t)weight_row<SWIGLU>(min(n0 + row, N - 1), F) * ldw + piece * 8 + k_begin;
     }
-#define RPO_DMA_SLAB(stage, kt_)                                                                        \
-    {                                                                                                   \
-        _Pragma("unroll") for (int j = 0; j < A_INST; ++j)                                              \
-            dma_load16(a_src[j] + (kt_) * kBK, lds_a + ((stage) * A_STAGE + (j * NW + wave) * 512) * 2); \
-        _Pragma("unroll") for (int j = 0; j < B_INST; ++j)                                              \
-            dma_load16(b_src[j] + (kt_) * kBK, lds_b + ((stage) * B_STAGE + (j * NW + wave) * 512) * 2); \
+    // slab s_ (clamped to the last one: loads past the end are redundant, never read) -> stage
+#define RPO_DMA_SLAB(s_)                                                                                 \
+    {                                                                                                    \
+        const int sl_ = (s_) < nk ? (s_) : nk - 1;                                                       \
+        const int st_ = (s_) % STAGES;                                                                   \
+        _Pragma("unroll") for (int j = 0; j < A_INST; ++j)                                               \
+            dma_load16(a_src[j] + sl_ * BK, lds_a + (st_ * A_STAGE + (j * NW + wave) * 512) * 2);        \
+        _Pragma("unroll") for (int j = 0; j < B_INST; ++j)                                               \
+            dma_load16(b_src[j] + sl_ * BK, lds_b + (st_ * B_STAGE + (j * NW + wave) * 512) * 2);        \
     }
 
     f32x16_t acc[MI][NI];
@@ -416,36 +436,41 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const bf16* __res
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-    // Fragment addressing: row = 32-aligned base + lane % 32, so g(row) depends on the lane only.
+    // Fragment addressing: row = 32-aligned base + lane % 32, so the swizzle depends on the lane only.
     const int frag_row = lane & 31;
-    const int frag_g = (lane & 7) ^ ((lane >> 3) & 1);
+    const int frag_g = lds_swizzle<BK>(frag_row);
     const int frag_half = lane >> 5;
+    // STAGES - 1 slabs are in flight ahead of the one being multiplied; after issuing slab
+    // kt + STAGES - 1 a wave waits until all but the newest STAGES - 2 slabs' loads have landed.
+    constexpr int kInFlight = (STAGES - 2) * (A_INST + B_INST);
     if (nk > 0) {
-        RPO_DMA_SLAB(0, 0);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int s0 = 0; s0 < STAGES - 1; ++s0) RPO_DMA_SLAB(s0);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kInFlight) : "memory");
         __syncthreads();
         for (int kt = 0; kt < nk; ++kt) {
-            const int stage = kt & 1;
-            if (kt + 1 < nk) RPO_DMA_SLAB(stage ^ 1, kt + 1);
-            const bf16* as = As + stage * A_STAGE + (wm * TM + frag_row) * kBK;
-            const bf16* bs = Bs + stage * B_STAGE + (wn * TN + frag_row) * kBK;
+            const int stage = kt % STAGES;
+            RPO_DMA_SLAB(kt + STAGES - 1);  // into the stage whose slab (kt - 1) everyone has finished reading
+            const bf16* as = As + stage * A_STAGE + (wm * TM + frag_row) * BK;
+            const bf16* bs = Bs + stage * B_STAGE + (wn * TN + frag_row) * BK;
 #pragma unroll
-            for (int ks = 0; ks < kBK / 16; ++ks) {
+            for (int ks = 0; ks < BK / 16; ++ks) {
                 const int piece = ((ks * 2 + frag_half) ^ frag_g) * 8;
                 bf16x8_t af[MI], bfr[NI];
 #pragma unroll
-                for (int i = 0; i < MI; ++i) af[i] = *(const bf16x8_t*)(as + i * 32 * kBK + piece);
+                for (int i = 0; i < MI; ++i) af[i] = *(const bf16x8_t*)(as + i * 32 * BK + piece);
 #pragma unroll
-                for (int j = 0; j < NI; ++j) bfr[j] = *(const bf16x8_t*)(bs + j * 32 * kBK + piece);
+                for (int j = 0; j < NI; ++j) bfr[j] = *(const bf16x8_t*)(bs + j * 32 * BK + piece);
 #pragma unroll
                 for (int i = 0; i < MI; ++i)
 #pragma unroll
                     for (int j = 0; j < NI; ++j)
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
             }
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kInFlight) : "memory");
             __syncthreads();
         }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // drain the redundant tail loads before LDS is released
     }
 #undef RPO_DMA_SLAB
     gemm_epilogue<MI, NI, TM, TN, EPI>(acc, Cv, ldc, M, N, m0, n0, wm, wn, lane);
@@ -572,6 +597,8 @@ int pick_splits(const GemmArgs& a, const TileCfg& t) {
 
 template <int BM, int BN, int WM, int WN, int EPI, bool SWIGLU>
 hipError_t launch_one(const GemmArgs& a, int splits, void* out, hipStream_t s) {
+    // direct-to-LDS pipeline shape: 64-deep slabs in two stages, or 32-deep slabs in four
+    constexpr int DBK = RPO_DMA_BK, DST = RPO_DMA_STAGES;
     const int gm = ceil_div(a.M, BM), gn = ceil_div(a.N, BN);
     // logical tile space padded to whole blocks of blk_m x blk_n tiles (see the kernel)
     const int blk_m = gm < 8 ? gm : 8, blk_n = 32 / blk_m;
@@ -582,8 +609,8 @@ hipError_t launch_one(const GemmArgs& a, int splits, void* out, hipStream_t s) {
     // direct-to-LDS loads need whole 64-deep slabs; path 2 keeps the register-staged kernel
     const bool dma = a.K % kBK == 0 && a.path != 2;
     if (dma) {
-        const size_t lds = (size_t)2 * (BM + BN) * kBK * sizeof(bf16);
-        auto kern = gemm_dma_kernel<BM, BN, WM, WN, EPI, SWIGLU>;
+        const size_t lds = (size_t)DST * (BM + BN) * DBK * sizeof(bf16);
+        auto kern = gemm_dma_kernel<BM, BN, WM, WN, EPI, SWIGLU, DBK, DST>;
         static bool attr_set = false;  // one flag per template instance
         if (!attr_set) {
             hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
