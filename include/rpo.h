@@ -153,11 +153,20 @@ int rpo_decode_step(rpo_batch *b, const int32_t *tokens_dev, int32_t n_rows,
  *   seq_id_dev  device uint64 [n_out_rows]: Philox stream id of each output row
  *   tokens_out_dev  device int32 [n_out_rows]
  *   logprob_out_dev device fp32 [n_out_rows] or NULL: log softmax(z/T)[token] (fp32 accuracy)
+ * Variable-length rollouts (the paper generates until end-of-sequence or the length cap,
+ * Sec. 4.1; Eq. 11 needs the response lengths):
+ *   eos_id            end-of-sequence token id, or < 0 for none
+ *   active_inout_dev  device uint8 [n_out_rows] or NULL.  A row with 0 is finished: nothing is
+ *                     drawn, its token is eos_id (0 if none) and its log-prob 0.  A live row that
+ *                     draws eos_id is set to 0 (pass the same array to rpo_decode_step).
+ *   lengths_inout_dev device int32 [n_out_rows] or NULL: incremented for every live row (the
+ *                     end-of-sequence token counts).
  * NaN logits give undefined tokens.  Errors: RPO_EINVAL (sizes, temperature <= 0). */
 int rpo_sample(const float *logits_dev, int32_t n_logit_rows, int32_t vocab, int64_t row_stride,
                const int32_t *row_map_dev, int32_t n_out_rows, float temperature, uint64_t seed,
                const uint64_t *seq_id_dev, uint32_t step, int32_t *tokens_out_dev,
-               float *logprob_out_dev, void *stream);
+               float *logprob_out_dev, int32_t eos_id, uint8_t *active_inout_dev,
+               int32_t *lengths_inout_dev, void *stream);
 
 /* log pi(o_j | q, o_<j) of every suffix token (the quantity the ratio of Eq. 7 is
  * made of), teacher-forced: for each rollout row r the suffix tokens are pushed

@@ -7,8 +7,9 @@ TEST INFRASTRUCTURE ONLY (see oracle/__init__.py).
 
 Readings: one m per question and step, shared by its G rollouts (the paper's
 Sec. 3.4 notes that the group shares the same response prefix); exactly m
-tokens are regenerated (synthetic models have no meaningful end-of-sequence
-token).  The oracle has no cache sharing: every rollout gets its own copy of
+tokens are regenerated unless an end-of-sequence id is given, in which case a
+rollout stops right after sampling it (the paper generates until end of
+sequence or the length cap, Sec. 4.1) and m is the cap.  The oracle has no cache sharing: every rollout gets its own copy of
 the prefix keys/values.
 """
 from __future__ import annotations
@@ -27,11 +28,12 @@ def cut(prompt: np.ndarray, cached: np.ndarray, m: int) -> np.ndarray:
 
 
 def suffix_rollout(shape, w, prompt, cached, m: int, n_rollouts: int,
-                   temperature: float, seed: int, seq_ids, n_tokens=None):
+                   temperature: float, seed: int, seq_ids, n_tokens=None, eos_id=None):
     """Generate `n_tokens` (default m) suffix tokens for each of the G rollouts.
 
     Returns dict(prefix, tokens [G, n], logits [G, n, V] fp32 as sampled from,
-    logprobs [G, n] fp64 of the sampled tokens at `temperature`).
+    logprobs [G, n] fp64 of the sampled tokens at `temperature`, lengths [G]).
+    Positions after an end-of-sequence token hold eos_id / zeros.
     """
     n = m if n_tokens is None else n_tokens
     prefix = cut(prompt, cached, m)
@@ -39,6 +41,9 @@ def suffix_rollout(shape, w, prompt, cached, m: int, n_rollouts: int,
     toks = np.zeros((n_rollouts, n), np.int32)
     lps = np.zeros((n_rollouts, n), np.float64)
     zs = np.zeros((n_rollouts, n, shape.vocab), np.float32)
+    lengths = np.zeros(n_rollouts, np.int64)
+    if eos_id is not None:
+        toks[:] = eos_id
     for i in range(n_rollouts):
         kv = kv0.copy()
         z = z0
@@ -47,6 +52,9 @@ def suffix_rollout(shape, w, prompt, cached, m: int, n_rollouts: int,
             zs[i, j] = z32
             toks[i, j], lps[i, j] = sampler.sample_row(z32, temperature, seed,
                                                        int(seq_ids[i]), j)
+            lengths[i] = j + 1
+            if eos_id is not None and toks[i, j] == eos_id:
+                break
             if j + 1 < n:
                 z = transformer.decode_step(shape, w, int(toks[i, j]), kv)
-    return dict(prefix=prefix, tokens=toks, logits=zs, logprobs=lps)
+    return dict(prefix=prefix, tokens=toks, logits=zs, logprobs=lps, lengths=lengths)

@@ -67,7 +67,7 @@ def lib() -> C.CDLL:
     L.rpo_prefill_prefix.argtypes = [vp, vp, C.POINTER(i32), vp, vp]
     L.rpo_kv_fork.argtypes = [vp, vp]
     L.rpo_decode_step.argtypes = [vp, vp, i32, vp, vp, vp]
-    L.rpo_sample.argtypes = [vp, i32, i32, i64, vp, i32, f32, u64, vp, u32, vp, vp, vp]
+    L.rpo_sample.argtypes = [vp, i32, i32, i64, vp, i32, f32, u64, vp, u32, vp, vp, i32, vp, vp, vp]
     L.rpo_suffix_logprobs.argtypes = [vp, vp, C.POINTER(i32), f32, vp, vp]
     L.grpo_advantages.argtypes = [vp, i32, i32, i32, f32, vp, vp]
     L.rpo_shape_rewards.argtypes = [vp, vp, i32, i32, f32, f32, f32, vp, vp]
@@ -229,7 +229,8 @@ def rpo_decode_step(batch: Batch, tokens_dev: torch.Tensor, n_rows: int, active_
 
 def rpo_sample(logits_dev: torch.Tensor, n_logit_rows: int, vocab: int, row_stride: int, row_map_dev,
                n_out_rows: int, temperature: float, seed: int, seq_id_dev: torch.Tensor, step: int,
-               tokens_out_dev: torch.Tensor, logprob_out_dev=None, stream=None) -> None:
+               tokens_out_dev: torch.Tensor, logprob_out_dev=None, stream=None, eos_id: int = -1,
+               active_inout_dev=None, lengths_inout_dev=None) -> None:
     if logits_dev.dtype != torch.float32 or tokens_out_dev.dtype != torch.int32:
         raise ValueError("logits must be float32, tokens int32")
     if logits_dev.numel() < (n_logit_rows - 1) * row_stride + vocab:
@@ -238,7 +239,8 @@ def rpo_sample(logits_dev: torch.Tensor, n_logit_rows: int, vocab: int, row_stri
         raise ValueError("seq_id_dev / tokens_out_dev smaller than n_out_rows")
     _check(lib().rpo_sample(logits_dev.data_ptr(), n_logit_rows, vocab, row_stride, _ptr(row_map_dev),
                             n_out_rows, temperature, seed, seq_id_dev.data_ptr(), step,
-                            tokens_out_dev.data_ptr(), _ptr(logprob_out_dev), _stream(stream)))
+                            tokens_out_dev.data_ptr(), _ptr(logprob_out_dev), eos_id, _ptr(active_inout_dev),
+                            _ptr(lengths_inout_dev), _stream(stream)))
 
 
 def rpo_suffix_logprobs(batch: Batch, suffix_tokens_dev: torch.Tensor, cu_suffix_host, temperature: float,

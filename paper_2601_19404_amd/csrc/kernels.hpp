@@ -156,6 +156,9 @@ struct SampleArgs {
     uint32_t step;
     int32_t* tokens_out;
     float* logprob_out;
+    int eos_id;          // < 0: no end-of-sequence token
+    uint8_t* active;     // in/out per output row, or NULL: all rows live
+    int32_t* lengths;    // in/out per output row (tokens generated so far), or NULL
 };
 hipError_t launch_sample(const SampleArgs& a, hipStream_t s);
 

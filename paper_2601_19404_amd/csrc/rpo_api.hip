@@ -760,7 +760,8 @@ extern "C" int rpo_suffix_logprobs(rpo_batch* b, const int32_t* suffix_tokens_de
 extern "C" int rpo_sample(const float* logits_dev, int32_t n_logit_rows, int32_t vocab, int64_t row_stride,
                           const int32_t* row_map_dev, int32_t n_out_rows, float temperature, uint64_t seed,
                           const uint64_t* seq_id_dev, uint32_t step, int32_t* tokens_out_dev,
-                          float* logprob_out_dev, void* stream) {
+                          float* logprob_out_dev, int32_t eos_id, uint8_t* active_inout_dev,
+                          int32_t* lengths_inout_dev, void* stream) {
     if (!logits_dev || !seq_id_dev || !tokens_out_dev) return fail(RPO_EINVAL, "rpo_sample: NULL argument");
     if (n_logit_rows < 1 || vocab < 1 || vocab > 262144 || row_stride < vocab || n_out_rows < 0)
         return fail(RPO_EINVAL, "rpo_sample: bad sizes (vocab 1..262144, row_stride >= vocab)");
@@ -780,6 +781,9 @@ extern "C" int rpo_sample(const float* logits_dev, int32_t n_logit_rows, int32_t
     a.step = step;
     a.tokens_out = tokens_out_dev;
     a.logprob_out = logprob_out_dev;
+    a.eos_id = eos_id >= vocab ? -1 : eos_id;
+    a.active = active_inout_dev;
+    a.lengths = lengths_inout_dev;
     HIP_TRY(timed(kKidSample, 0.0, (double)n_out_rows * vocab * 4.0, (hipStream_t)stream,
                   [&] { return launch_sample(a, (hipStream_t)stream); }));
     return RPO_OK;

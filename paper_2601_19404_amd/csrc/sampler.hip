@@ -105,6 +105,13 @@ __global__ __launch_bounds__(256) void sample_kernel(SampleArgs a) {
     __shared__ uint64_t pick_rem, row_total;
     const int r = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (a.active && !a.active[r]) {  // finished rollout: no draw, the output is padding
+        if (tid == 0) {
+            a.tokens_out[r] = a.eos_id >= 0 ? a.eos_id : 0;
+            if (a.logprob_out) a.logprob_out[r] = 0.f;
+        }
+        return;
+    }
     const int src = a.row_map ? a.row_map[r] : r;
     const float* z = a.logits + (int64_t)src * a.row_stride;
     const int V = a.vocab;
@@ -195,6 +202,8 @@ __global__ __launch_bounds__(256) void sample_kernel(SampleArgs a) {
                     run += q[e];
                 }
                 a.tokens_out[r] = tok;
+                if (a.lengths) a.lengths[r] += 1;
+                if (a.active && a.eos_id >= 0 && tok == a.eos_id) a.active[r] = 0;
                 if (a.logprob_out) {
                     const float x = ((z[tok] - zmax) * a.inv_t);
                     a.logprob_out[r] = x - (float)(log((double)row_total) - 40.0 * 0.6931471805599453);

@@ -39,18 +39,21 @@ class RolloutResult:
     cu_len: np.ndarray
     n_generated: int
     logits: list | None = None    # per step: fp32 [rows, V] copies when keep_logits
+    lengths: torch.Tensor | None = None   # int32 [B] tokens generated per rollout (with eos_id)
 
 
 def suffix_rollout(batch: rpo.Batch, prompts, cached, m, temperature: float, seed: int,
                    seq_ids: torch.Tensor, keep_logits: bool | int = False, stream=None,
-                   marks: list | None = None) -> RolloutResult:
+                   marks: list | None = None, eos_id: int | None = None) -> RolloutResult:
     """Regenerate m_k tokens for each of the G rollouts of every group.
 
     Groups must be ordered by decreasing m (see order_by_suffix_length) so that the
     live rows are always a leading block.  seq_ids: uint64-valued int64 device tensor
     [B], the Philox stream id of each rollout row.  keep_logits: True keeps a copy of every
     step's logits (tests), an integer n only those of the first n steps.  marks: if a list,
-    (name, torch.cuda.Event) pairs are appended at the phase boundaries (benchmark timing)."""
+    (name, torch.cuda.Event) pairs are appended at the phase boundaries (benchmark timing).
+    eos_id: if given, a rollout that samples it stops there (its later tokens are eos_id padding,
+    it appends no more K/V) and the per-rollout lengths are returned; m is then the cap."""
     cfg = batch.model.cfg
     G, ng = batch.G, batch.n_groups
     B = ng * G
@@ -66,6 +69,12 @@ def suffix_rollout(batch: rpo.Batch, prompts, cached, m, temperature: float, see
     out_tokens = torch.zeros((max_m, B), dtype=torch.int32, device="cuda")
     out_lp = torch.zeros((max_m, B), dtype=torch.float32, device="cuda")
     row_map = torch.arange(B, dtype=torch.int32, device="cuda") // G
+    active = lengths = None
+    eos = -1
+    if eos_id is not None:
+        eos = int(eos_id)
+        active = torch.ones(B, dtype=torch.uint8, device="cuda")
+        lengths = torch.zeros(B, dtype=torch.int32, device="cuda")
     kept = [] if keep_logits else None
     n_keep = max_m if keep_logits is True else int(keep_logits)
 
@@ -86,21 +95,21 @@ def suffix_rollout(batch: rpo.Batch, prompts, cached, m, temperature: float, see
     if max_m > 0:
         n0 = live_groups[0] * G
         rpo.rpo_sample(last_logits, ng, V, V, row_map, n0, temperature, seed, seq_ids, 0,
-                       out_tokens[0], out_lp[0], stream)
+                       out_tokens[0], out_lp[0], stream, eos, active, lengths)
         if n_keep > 0:
             kept.append(last_logits.clone())
     for j in range(1, max_m):
         n = live_groups[j] * G
         if n == 0:
             break
-        rpo.rpo_decode_step(batch, out_tokens[j - 1], n, None, logits, stream)
+        rpo.rpo_decode_step(batch, out_tokens[j - 1], n, active, logits, stream)
         rpo.rpo_sample(logits, n, V, V, None, n, temperature, seed, seq_ids, j, out_tokens[j],
-                       out_lp[j], stream)
+                       out_lp[j], stream, eos, active, lengths)
         if j < n_keep:
             kept.append(logits[:n].clone())
     mark("decode")
     return RolloutResult(out_tokens.t().contiguous(), out_lp.t().contiguous(), m, cu,
-                         int(m.sum()) * G, kept)
+                         int(m.sum()) * G, kept, lengths)
 
 
 def suffix_index(m, G: int, max_m: int):

@@ -267,3 +267,67 @@ def test_state_and_argument_errors(rpo):
         rpo.rpo_decode_step(batch, tok, 8, None, logits)              # beyond max_suffix = 2
     assert e.value.code == rpo.RPO_ESTATE
     torch.cuda.synchronize()
+
+
+def test_variable_length_rollouts_eos_and_shaped_rewards(rpo):
+    """A rollout that samples the end-of-sequence id stops there: same tokens as the unconstrained
+    run up to the stop, padding after it, per-rollout lengths, the other rollouts untouched
+    (bit-identical logits); the lengths then drive Eq. 11 and Eq. 7."""
+    from oracle import reward_shaping as ors
+    from paper_2601_19404_amd import rollout
+    rpo.rpo_set_kernel_path(0)
+    mcfg = synth.TINY
+    w = synth.make_weights(mcfg, seed=77)
+    model = rpo.rpo_model_create(mcfg, util.to_device(w))
+    p, a, m = tiny_workload(ng=3, seed=5)
+    order = rollout.order_by_suffix_length(m)
+    p, a, m = [p[i] for i in order], [a[i] for i in order], np.asarray(m)[order]
+    G, ng = 4, 3
+    seq_ids = util.seq_ids_dev(ng * G, base=50)
+
+    def run(eos):
+        batch = rpo.rpo_batch_create(model, ng, G, 80, 16, 16, 128)
+        res = rollout.suffix_rollout(batch, p, a, m, 1.0, 9, seq_ids, keep_logits=True, eos_id=eos)
+        torch.cuda.synchronize()
+        return res
+
+    free = run(None)
+    ft = free.tokens.cpu().numpy()
+    eos = int(ft[5, 3])                                   # rollout 5 (group 1) stops after its 4th token
+    res = run(eos)
+    tk, ln = res.tokens.cpu().numpy(), res.lengths.cpu().numpy()
+    for r in range(ng * G):
+        mg = int(m[r // G])
+        hit = np.flatnonzero(ft[r, :mg] == eos)
+        n = hit[0] + 1 if len(hit) else mg
+        assert ln[r] == n
+        np.testing.assert_array_equal(tk[r, :n], ft[r, :n])
+        assert np.all(tk[r, n:mg] == eos)
+    assert ln[5] == 4
+    # rows that never stop see bit-identical logits at every step
+    never = [r for r in range(ng * G) if ln[r] == m[r // G]]
+    assert never
+    for j in range(1, int(m.max())):
+        rows = [r for r in never if r < res.logits[j].shape[0] and j < m[r // G]]
+        if rows:
+            np.testing.assert_array_equal(res.logits[j][rows].cpu().numpy(), free.logits[j][rows].cpu().numpy())
+    # oracle parity of the stopped rollout: its logits rows up to the stop
+    w_np = synth.weights_to_numpy(w)
+    shape = util.oracle_shape(mcfg)
+    g = 5 // G
+    prefix = np.concatenate([p[g], a[g][:64 - int(m[g])]])
+    ref = T.teacher_forced_logits(shape, w_np, prefix, tk[5, :4])
+    for j in range(4):
+        got = res.logits[j][g if j == 0 else 5].cpu().numpy()
+        assert np.abs(got - ref[j]).max() < 1e-4
+    # lengths -> shaped rewards -> advantages
+    rewards = np.ones((ng, G), np.float32)
+    shaped = torch.empty(ng, G, dtype=torch.float32, device="cuda")
+    rpo.rpo_shape_rewards(torch.from_numpy(rewards).cuda(), res.lengths, ng, G, 0.05, 0.5, 1.0, shaped)
+    adv = torch.empty(ng, G, dtype=torch.float32, device="cuda")
+    rpo.grpo_advantages(shaped, ng, G, 0, 0.0, adv)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(shaped.cpu().numpy(), ors.shape_rewards(rewards, ln.reshape(ng, G), 0.05, 0.5, 1.0),
+                               atol=1e-6)
+    np.testing.assert_array_equal(adv.cpu().numpy(), oadv.grpo_advantages(shaped.cpu().numpy()))
+    assert adv.cpu().numpy()[1, 1] > 0          # the rollout that stopped early is preferred in its group

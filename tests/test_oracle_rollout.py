@@ -63,3 +63,19 @@ def test_token_reduction_accounting():
     assert 0.05 <= frac <= 0.10
     paper_frac = 145.88 / 2689.51
     assert 0.04 < paper_frac < 0.07
+
+
+def test_rollout_stops_at_end_of_sequence():
+    shape, w = _tiny()
+    wl = synth.make_workload(synth.C0)
+    m = int(wl.m[0])
+    free = rollout.suffix_rollout(shape, w, wl.prompts[0], wl.cached[0], m, 4, 1.0, 3, wl.seq_ids[:4])
+    eos = int(free["tokens"][1, 2])                     # rollout 1 will hit it at step 2
+    out = rollout.suffix_rollout(shape, w, wl.prompts[0], wl.cached[0], m, 4, 1.0, 3, wl.seq_ids[:4], eos_id=eos)
+    assert out["lengths"][1] == 3
+    for i in range(4):
+        n = int(out["lengths"][i])
+        np.testing.assert_array_equal(out["tokens"][i, :n], free["tokens"][i, :n])   # same draws until the stop
+        assert np.all(out["tokens"][i, n:] == eos)
+        hit = np.flatnonzero(free["tokens"][i] == eos)
+        assert n == (hit[0] + 1 if len(hit) else m)
