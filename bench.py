@@ -54,11 +54,21 @@ def algorithmic_decode_bytes(st) -> float:
     return total
 
 
-def build_case(workload: str, n_groups: int | None, max_rows: int):
+def build_case(workload: str, n_groups: int | None, max_rows: int, G: int | None = None,
+               temperature: float | None = None, trunc_max: int | None = None):
+    import dataclasses
     import torch
     from paper_2601_19404_amd import binding as rpo
     from paper_2601_19404_amd import rollout, synth
     cfg = synth.CONFIGS[workload]
+    # the paper's own sampling settings (Sec. 4.1, Fig. 3): G in {6, 8, 16}, temperature 0.7,
+    # m ~ U{0..L} with L in {300, 500, 800}
+    if G is not None:
+        cfg = dataclasses.replace(cfg, G=G)
+    if temperature is not None:
+        cfg = dataclasses.replace(cfg, temperature=temperature)
+    if trunc_max is not None:
+        cfg = dataclasses.replace(cfg, m_lo=0, m_hi=trunc_max)
     mc = cfg.model
     w = synth.make_weights(mc, seed=1234, device="cuda")
     model = rpo.rpo_model_create(mc, w)
@@ -70,7 +80,7 @@ def build_case(workload: str, n_groups: int | None, max_rows: int):
     rewards = wl.rewards[order]
     ng, G = len(prompts), cfg.G
     max_prefix = cfg.prompt_len + cfg.traj_len - int(m.min())
-    max_suffix = int(m.max())
+    max_suffix = max(int(m.max()), 1)
     max_rows = max(max_rows, max_prefix, ng * G, max_suffix)
     page = 64 if mc.dtype == "bf16" else 16
     batch = rpo.rpo_batch_create(model, ng, G, max_prefix, max_suffix, page, max_rows)
@@ -206,6 +216,10 @@ def main():
     ap.add_argument("--workload", default="C1", choices=["C0", "C1", "C2", "C3", "C4"])
     ap.add_argument("--groups", type=int, default=None, help="override the number of groups (debugging)")
     ap.add_argument("--max-rows", type=int, default=16384)
+    ap.add_argument("--G", type=int, default=None, help="rollouts per group (paper: 6, 8, 16)")
+    ap.add_argument("--temperature", type=float, default=None, help="sampling temperature (paper: 0.7)")
+    ap.add_argument("--trunc-max", type=int, default=None,
+                    help="draw m ~ U{0..L} as in Eq. 3 (paper: L = 300, 500, 800) instead of the 5-10 %% cut")
     ap.add_argument("--profile-kernel", default="gemm256",
                     help="kernel whose launches are timed with HIP events for the roofline object")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -250,7 +264,7 @@ def main():
     if args.workload == "C4":
         run_c4(args)
         return
-    st = build_case(args.workload, args.groups, args.max_rows)
+    st = build_case(args.workload, args.groups, args.max_rows, args.G, args.temperature, args.trunc_max)
     cfg = st["cfg"]
     for i in range(args.warmup):
         one_step(st, seed=100 + i)
@@ -298,7 +312,7 @@ def main():
                            prompt_len=cfg.prompt_len, traj_len=cfg.traj_len,
                            suffix_len_range=[int(st["m"].min()), int(st["m"].max())],
                            generated_tokens_per_step=int(n_gen), page_tokens=st["page"],
-                           temperature=cfg.temperature),
+                           temperature=cfg.temperature, mean_suffix_len=float(st["m"].mean())),
                phase_ms_per_step={k: round(v, 2) for k, v in phases.items()},
                host_enqueue_ms_per_step={k: round(v, 2) for k, v in enqueue.items()},
                decode_tokens_per_s=(n_gen - st["ng"] * st["G"]) / (phases.get("decode", float("nan")) / 1e3),

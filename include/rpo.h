@@ -191,6 +191,23 @@ int rpo_suffix_logprobs(rpo_batch *b, const int32_t *suffix_tokens_dev, const in
 int grpo_advantages(const float *rewards_dev, int32_t n_groups, int32_t G, int32_t ddof, float eps,
                     float *adv_out_dev, void *stream);
 
+/* Forward value of the objective, Eq. 5-7: per token l = min(r A, clip(r, 1 - eps_clip, 1 + eps_clip) A)
+ * with r = exp(lp_new - lp_old) (the ratio of Eq. 7) and A the rollout's advantage; per group
+ * J = mean_i [ (sum_j l_ij - beta * sum_j (lp_new_ij - lp_ref_ij)) / |o_i| ].  The KL term sits
+ * outside the min (Eq. 5) and uses the per-token sample estimate of E[log pi - log pi_ref] (App. B
+ * names no estimator).  The log-probs come from rpo_suffix_logprobs under the respective weights.
+ *   lp_new_dev, lp_old_dev device fp32, packed per token like rpo_suffix_logprobs' output
+ *   lp_ref_dev   same, or NULL when beta == 0
+ *   cu_suffix_dev device int32 [n_groups*G + 1] cumulative suffix lengths (DEVICE copy)
+ *   adv_dev       device fp32 [n_groups*G] (grpo_advantages' output)
+ *   token_out_dev device fp32 packed per token, or NULL
+ *   rollout_scratch_dev device fp64 [n_groups*G] scratch; group_out_dev device fp32 [n_groups]
+ * Empty responses contribute 0.  Errors: RPO_EINVAL. */
+int rpo_objective_forward(const float *lp_new_dev, const float *lp_old_dev, const float *lp_ref_dev,
+                          const int32_t *cu_suffix_dev, const float *adv_dev, int32_t n_groups, int32_t G,
+                          float eps_clip, float beta, float *token_out_dev, double *rollout_scratch_dev,
+                          float *group_out_dev, void *stream);
+
 /* Length-aware reward shaping, Eq. 11 (Sec. 3.4): R_i = clip(r_i / (1 + exp(-alpha (l_ref - len_i))),
  * lo, hi) with l_ref the mean response length of the group; the paper uses lo 0.5, hi 1,
  * alpha 0.01 (Sec. 4.1).  Reading: applied to positive rewards only, r_i <= 0 gives R_i = 0

@@ -70,6 +70,7 @@ def lib() -> C.CDLL:
     L.rpo_sample.argtypes = [vp, i32, i32, i64, vp, i32, f32, u64, vp, u32, vp, vp, i32, vp, vp, vp]
     L.rpo_suffix_logprobs.argtypes = [vp, vp, C.POINTER(i32), f32, vp, vp]
     L.grpo_advantages.argtypes = [vp, i32, i32, i32, f32, vp, vp]
+    L.rpo_objective_forward.argtypes = [vp, vp, vp, vp, vp, i32, i32, f32, f32, vp, vp, vp, vp]
     L.rpo_shape_rewards.argtypes = [vp, vp, i32, i32, f32, f32, f32, vp, vp]
     L.rpo_gemm_nt.argtypes = [vp, i64, vp, i64, vp, i64, i32, i32, i32, i32, i32, vp, sz, vp]
     L.rpo_set_kernel_path.argtypes = [C.c_int]
@@ -78,7 +79,7 @@ def lib() -> C.CDLL:
                                    C.POINTER(C.c_double)]
     for name in ("rpo_model_create", "rpo_batch_create", "rpo_prefill_prefix", "rpo_kv_fork",
                  "rpo_decode_step", "rpo_sample", "rpo_suffix_logprobs", "grpo_advantages",
-                 "rpo_shape_rewards", "rpo_gemm_nt", "rpo_set_kernel_path", "rpo_profile_start", "rpo_profile_stop"):
+                 "rpo_shape_rewards", "rpo_objective_forward", "rpo_gemm_nt", "rpo_set_kernel_path", "rpo_profile_start", "rpo_profile_stop"):
         getattr(L, name).restype = C.c_int
     _lib = L
     return L
@@ -87,7 +88,7 @@ def lib() -> C.CDLL:
 EXPORTS = ("rpo_model_create", "rpo_model_destroy", "rpo_kv_pool_bytes", "rpo_workspace_bytes",
            "rpo_batch_create", "rpo_batch_destroy", "rpo_prefill_prefix", "rpo_kv_fork",
            "rpo_decode_step", "rpo_sample", "rpo_suffix_logprobs", "grpo_advantages",
-           "rpo_shape_rewards", "rpo_last_error", "rpo_gemm_nt", "rpo_set_kernel_path", "rpo_profile_start",
+           "rpo_shape_rewards", "rpo_objective_forward", "rpo_last_error", "rpo_gemm_nt", "rpo_set_kernel_path", "rpo_profile_start",
            "rpo_profile_stop")
 
 
@@ -263,6 +264,21 @@ def grpo_advantages(rewards_dev: torch.Tensor, n_groups: int, G: int, ddof: int,
         raise ValueError("rewards / advantages smaller than n_groups x G")
     _check(lib().grpo_advantages(rewards_dev.data_ptr(), n_groups, G, ddof, eps, adv_out_dev.data_ptr(),
                                  _stream(stream)))
+
+
+def rpo_objective_forward(lp_new_dev, lp_old_dev, lp_ref_dev, cu_suffix_dev, adv_dev, n_groups: int, G: int,
+                          eps_clip: float, beta: float, token_out_dev, group_out_dev, stream=None) -> None:
+    for t, nm in ((lp_new_dev, "lp_new_dev"), (lp_old_dev, "lp_old_dev"), (adv_dev, "adv_dev"),
+                  (group_out_dev, "group_out_dev")):
+        _dev(t, torch.float32, nm)
+    _dev(cu_suffix_dev, torch.int32, "cu_suffix_dev")
+    if cu_suffix_dev.numel() < n_groups * G + 1 or adv_dev.numel() < n_groups * G or group_out_dev.numel() < n_groups:
+        raise ValueError("buffers do not match n_groups x G")
+    scratch = torch.empty(max(n_groups * G, 1), dtype=torch.float64, device=lp_new_dev.device)
+    _check(lib().rpo_objective_forward(lp_new_dev.data_ptr(), lp_old_dev.data_ptr(), _ptr(lp_ref_dev),
+                                       cu_suffix_dev.data_ptr(), adv_dev.data_ptr(), n_groups, G, eps_clip, beta,
+                                       _ptr(token_out_dev), scratch.data_ptr(), group_out_dev.data_ptr(),
+                                       _stream(stream)))
 
 
 def rpo_shape_rewards(rewards_dev: torch.Tensor, lengths_dev: torch.Tensor, n_groups: int, G: int,

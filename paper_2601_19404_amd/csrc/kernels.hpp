@@ -166,6 +166,9 @@ hipError_t launch_sample(const SampleArgs& a, hipStream_t s);
 hipError_t launch_lse_gather(const float* logits, int64_t row_stride, int vocab, const int32_t* target,
                              float inv_t, float* out, int rows, hipStream_t s);
 
+hipError_t launch_objective(const float* lp_new, const float* lp_old, const float* lp_ref, const int32_t* cu,
+                            const float* adv, int n_groups, int G, float eps_clip, float beta, float* tok_out,
+                            double* per_rollout, float* j_out, hipStream_t s);
 hipError_t launch_shape_rewards(const float* rewards, const int32_t* lengths, int n_groups, int G, float alpha,
                                 float lo, float hi, float* out, hipStream_t s);
 hipError_t launch_advantages(const float* rewards, int n_groups, int G, int ddof, float eps, float* adv,

@@ -799,6 +799,21 @@ extern "C" int grpo_advantages(const float* rewards_dev, int32_t n_groups, int32
     return RPO_OK;
 }
 
+extern "C" int rpo_objective_forward(const float* lp_new_dev, const float* lp_old_dev, const float* lp_ref_dev,
+                                     const int32_t* cu_suffix_dev, const float* adv_dev, int32_t n_groups,
+                                     int32_t G, float eps_clip, float beta, float* token_out_dev,
+                                     double* rollout_scratch_dev, float* group_out_dev, void* stream) {
+    if (!lp_new_dev || !lp_old_dev || !cu_suffix_dev || !adv_dev || !rollout_scratch_dev || !group_out_dev)
+        return fail(RPO_EINVAL, "rpo_objective_forward: NULL argument");
+    if (n_groups < 0 || G < 1) return fail(RPO_EINVAL, "rpo_objective_forward: bad sizes");
+    if (!(eps_clip >= 0.f) || !(beta >= 0.f)) return fail(RPO_EINVAL, "rpo_objective_forward: eps_clip, beta must be >= 0");
+    if (beta > 0.f && !lp_ref_dev) return fail(RPO_EINVAL, "rpo_objective_forward: beta > 0 needs reference log-probs");
+    HIP_TRY(launch_objective(lp_new_dev, lp_old_dev, beta > 0.f ? lp_ref_dev : nullptr, cu_suffix_dev, adv_dev,
+                             n_groups, G, eps_clip, beta, token_out_dev, rollout_scratch_dev, group_out_dev,
+                             (hipStream_t)stream));
+    return RPO_OK;
+}
+
 extern "C" int rpo_shape_rewards(const float* rewards_dev, const int32_t* lengths_dev, int32_t n_groups, int32_t G,
                                  float alpha, float lo, float hi, float* shaped_out_dev, void* stream) {
     if (!rewards_dev || !lengths_dev || !shaped_out_dev) return fail(RPO_EINVAL, "rpo_shape_rewards: NULL argument");

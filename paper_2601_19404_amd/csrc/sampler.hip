@@ -320,6 +320,56 @@ __global__ __launch_bounds__(64) void shape_rewards_kernel(const float* __restri
     }
 }
 
+// Eq. 5-7 of the paper, forward value.  One thread per rollout walks its tokens (fp64):
+// surrogate l = min(r A, clip(r, 1 - eps, 1 + eps) A), r = exp(lp_new - lp_old); the rollout's
+// share is (sum l - beta * sum (lp_new - lp_ref)) / |o|.  A second kernel averages each group.
+__global__ __launch_bounds__(64) void objective_rollout_kernel(const float* __restrict__ lp_new,
+                                                               const float* __restrict__ lp_old,
+                                                               const float* __restrict__ lp_ref,
+                                                               const int32_t* __restrict__ cu,
+                                                               const float* __restrict__ adv, int n_rollouts,
+                                                               float eps_clip, float beta,
+                                                               float* __restrict__ tok_out,
+                                                               double* __restrict__ per_rollout) {
+    const int r = blockIdx.x * 64 + threadIdx.x;
+    if (r >= n_rollouts) return;
+    const int lo = cu[r], hi = cu[r + 1];
+    const double a = (double)adv[r], e = (double)eps_clip, b = (double)beta;
+    double s = 0.0, kl = 0.0;
+    for (int t = lo; t < hi; ++t) {
+        const double ln = (double)lp_new[t];
+        const double ratio = exp(ln - (double)lp_old[t]);
+        const double rc = fmin(fmax(ratio, 1.0 - e), 1.0 + e);
+        const double l = fmin(ratio * a, rc * a);
+        if (tok_out) tok_out[t] = (float)l;
+        s += l;
+        if (lp_ref) kl += ln - (double)lp_ref[t];
+    }
+    per_rollout[r] = hi > lo ? (s - b * kl) / (double)(hi - lo) : 0.0;
+}
+
+__global__ __launch_bounds__(64) void objective_group_kernel(const double* __restrict__ per_rollout, int n_groups,
+                                                             int G, float* __restrict__ j_out) {
+    const int k = blockIdx.x * 64 + threadIdx.x;
+    if (k >= n_groups) return;
+    double acc = 0.0;
+    for (int i = 0; i < G; ++i) acc += per_rollout[(int64_t)k * G + i];
+    j_out[k] = (float)(acc / (double)G);
+}
+
+hipError_t launch_objective(const float* lp_new, const float* lp_old, const float* lp_ref, const int32_t* cu,
+                            const float* adv, int n_groups, int G, float eps_clip, float beta, float* tok_out,
+                            double* per_rollout, float* j_out, hipStream_t s) {
+    const int n = n_groups * G;
+    if (n <= 0) return hipSuccess;
+    objective_rollout_kernel<<<ceil_div(n, 64), 64, 0, s>>>(lp_new, lp_old, lp_ref, cu, adv, n, eps_clip, beta,
+                                                           tok_out, per_rollout);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    objective_group_kernel<<<ceil_div(n_groups, 64), 64, 0, s>>>(per_rollout, n_groups, G, j_out);
+    return hipGetLastError();
+}
+
 hipError_t launch_shape_rewards(const float* rewards, const int32_t* lengths, int n_groups, int G, float alpha,
                                 float lo, float hi, float* out, hipStream_t s) {
     if (n_groups <= 0) return hipSuccess;

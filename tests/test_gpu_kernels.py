@@ -211,3 +211,31 @@ def test_reward_shaping_then_advantages(rpo):
         np.testing.assert_array_equal(adv.cpu().numpy(), oadv.grpo_advantages(got))
     with pytest.raises(rpo.RpoError):
         rpo.rpo_shape_rewards(out, torch.zeros(ng, g, dtype=torch.int32, device="cuda"), ng, g, 0.0, 0.5, 1.0, out)
+
+
+def test_objective_forward(rpo):
+    """Eq. 5-7 forward on the GPU against the oracle (fp64 on both sides: 1e-6 after the fp32 store)."""
+    from oracle import objective as oo
+    rng = np.random.default_rng(8)
+    ng, g = 9, 6
+    lens = rng.integers(0, 40, size=ng * g)
+    lens[3] = 0
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    n = int(cu[-1])
+    lp_old = (-rng.random(n) * 8).astype(np.float32)
+    lp_new = (lp_old + rng.normal(size=n) * 0.3).astype(np.float32)
+    lp_ref = (lp_old + rng.normal(size=n) * 0.2).astype(np.float32)
+    adv = rng.normal(size=ng * g).astype(np.float32)
+    dev = lambda a: torch.from_numpy(a).cuda()
+    for beta, ref in ((0.0, None), (0.04, lp_ref)):
+        tok = torch.empty(n, dtype=torch.float32, device="cuda")
+        j = torch.empty(ng, dtype=torch.float32, device="cuda")
+        rpo.rpo_objective_forward(dev(lp_new), dev(lp_old), None if ref is None else dev(ref), dev(cu), dev(adv),
+                                  ng, g, 0.2, beta, tok, j)
+        torch.cuda.synchronize()
+        tok_ref, j_ref = oo.group_objective(lp_new, lp_old, ref, cu, adv, g, 0.2, beta)
+        np.testing.assert_allclose(tok.cpu().numpy(), tok_ref, rtol=1e-6, atol=1e-7)
+        np.testing.assert_allclose(j.cpu().numpy(), j_ref, rtol=1e-6, atol=1e-7)
+    with pytest.raises(rpo.RpoError):
+        rpo.rpo_objective_forward(dev(lp_new), dev(lp_old), None, dev(cu), dev(adv), ng, g, 0.2, 0.1,
+                                  None, torch.empty(ng, device="cuda"))

@@ -69,3 +69,26 @@ def test_reward_shaping_closed_forms():
     assert out[0, 0] == 0 and out[0, 3] == 0 and out[0, 2] == 1.0
     # alpha -> small: every correct answer -> r / 2 -> 0.5 after the clip
     np.testing.assert_allclose(ors.shape_rewards(r, [[1, 50, 90, 400]], alpha=1e-9), 0.5, atol=1e-6)
+
+
+def test_objective_closed_forms():
+    from oracle import objective as oo
+    # ratio 1 (same policy), no KL: J = mean advantage-weighted 1 = mean of A_i -> 0 for standardised A
+    cu = np.array([0, 3, 5, 9, 10])
+    lp = np.log(np.full(10, 0.25)).astype(np.float32)
+    adv = np.array([1.0, -1.0, 1.0, -1.0], np.float32)
+    tok, j = oo.group_objective(lp, lp, None, cu, adv, 2, 0.2, 0.0)
+    np.testing.assert_allclose(tok, np.repeat(adv, np.diff(cu)))
+    np.testing.assert_allclose(j, [0.0, 0.0], atol=1e-12)
+    # clipping: r = 2 with eps 0.2.  A > 0 -> min(2A, 1.2A) = 1.2A ; A < 0 -> min(2A, 1.2A) = 2A
+    assert abs(oo.token_surrogate(math.log(2.0), 0.0, 1.0, 0.2) - 1.2) < 1e-12
+    assert abs(oo.token_surrogate(math.log(2.0), 0.0, -1.0, 0.2) + 2.0) < 1e-12
+    # r = 0.5: A > 0 -> min(0.5A, 0.8A) = 0.5A ; A < 0 -> min(-0.5, -0.8) = -0.8
+    assert abs(oo.token_surrogate(math.log(0.5), 0.0, 1.0, 0.2) - 0.5) < 1e-12
+    assert abs(oo.token_surrogate(math.log(0.5), 0.0, -1.0, 0.2) + 0.8) < 1e-12
+    # KL term: lp_new - lp_ref = 0.1 on every token, beta 0.5 -> J drops by 0.05; empty rollout counts 0
+    cu2 = np.array([0, 4, 4])
+    lp2 = np.zeros(4, np.float32)
+    _, j0 = oo.group_objective(lp2, lp2, lp2, cu2, np.array([1.0, 1.0], np.float32), 2, 0.2, 0.5)
+    _, j1 = oo.group_objective(lp2, lp2, lp2 - np.float32(0.1), cu2, np.array([1.0, 1.0], np.float32), 2, 0.2, 0.5)
+    assert abs(j0[0] - 0.5) < 1e-12 and abs((j0[0] - j1[0]) - 0.5 * 0.5 * np.float32(0.1)) < 1e-9
