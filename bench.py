@@ -24,7 +24,7 @@ sys.path.insert(0, ROOT)
 PEAK = {"hbm": (8000.0, "GB/s"), "mfma": (2500.0, "TFLOP/s")}
 # HBM-side bytes per launch of the dominant kernel's heaviest launch (prefill gate/up projection,
 # M=16384, N=17920, K=1536, SwiGLU epilogue), from two rocprofv3 --pmc runs (FETCH_SIZE x 2.0 and
-# WRITE_SIZE x 1.0 after calibration against a 1 GiB copy): profiles/gemm_hbm_traffic_pmc.txt.
+# WRITE_SIZE x 1.0 after calibration against a 1 GiB copy).
 GEMM256_TRAFFIC = dict(launch="prefill gate/up projection M=16384 N=17920 K=1536", read_bytes=1340.4e6,
                        write_bytes=293.6e6, algorithmic_bytes=105.4e6 + 293.6e6)
 KERNEL_BOUND = {"gemm256": "mfma", "gemm256x128": "mfma", "gemm128": "mfma", "gemm64": "mfma",
@@ -32,7 +32,7 @@ KERNEL_BOUND = {"gemm256": "mfma", "gemm256x128": "mfma", "gemm128": "mfma", "ge
 
 
 def algorithmic_decode_bytes(st) -> float:
-    """HBM bytes the decode loop must move (SURVEY 8(d) accounting): per step the layer and
+    """HBM bytes the decode loop must move: per step the layer and
     LM-head weights once, the shared prefix KV once per live GROUP, each live rollout's private
     KV, the new token's KV write, and the logits written by the LM head and read by the sampler."""
     cfg = st["cfg"]

@@ -144,7 +144,7 @@ def tiny_workload(ng=2, seed=1):
 
 
 def test_c0_tiny_fp32_end_to_end(rpo):
-    """BASELINE config 0 exactly: 2 prompts x G=4, prompt 16, answer 64 cut in [48, 56]."""
+    """The tiny benchmark configuration exactly: 2 prompts x G=4, prompt 16, answer 64 cut in [48, 56]."""
     p, a, m = tiny_workload()
     worst, res = run_case(rpo, synth.TINY, p, a, m, G=4, page=16)
     assert res.n_generated == int(m.sum()) * 4
