@@ -516,21 +516,32 @@ __global__ __launch_bounds__(256) void gemm_splitk_reduce_norm_kernel(const floa
                                                                       int M, int N, float* __restrict__ X,
                                                                       int64_t ldc, const bf16* __restrict__ gain,
                                                                       float eps, bf16* __restrict__ H) {
-    constexpr int kMaxPer = 32;  // N <= 8192
+    // N is a multiple of 4 (checked by the launcher): each thread owns float4 column groups
+    // tid, tid + 256, ... of the row, at most 8 of them (N <= 8192).
+    constexpr int kMaxVec = 8;
     __shared__ float part[4];
     const int m = blockIdx.x, tid = threadIdx.x;
     const int64_t plane = (int64_t)M * N;
-    float v[kMaxPer];
+    const int nvec = N >> 2;
+    float4 v[kMaxVec];
     float ss = 0.f;
+    float4* xrow = (float4*)(X + (int64_t)m * ldc);
+    const float4* prow = (const float4*)(P + (int64_t)m * N);
 #pragma unroll
-    for (int i = 0; i < kMaxPer; ++i) {
+    for (int i = 0; i < kMaxVec; ++i) {
         const int c = tid + i * 256;
-        if (c < N) {
-            float acc = X[(int64_t)m * ldc + c];
-            for (int z = 0; z < splits; ++z) acc += P[z * plane + (int64_t)m * N + c];
-            X[(int64_t)m * ldc + c] = acc;
+        if (c < nvec) {
+            float4 acc = xrow[c];
+            for (int z = 0; z < splits; ++z) {
+                const float4 p = prow[(z * plane >> 2) + c];
+                acc.x += p.x;
+                acc.y += p.y;
+                acc.z += p.z;
+                acc.w += p.w;
+            }
+            xrow[c] = acc;
             v[i] = acc;
-            ss += acc * acc;
+            ss += (acc.x * acc.x + acc.y * acc.y) + (acc.z * acc.z + acc.w * acc.w);
         }
     }
     ss = wave_sum(ss);
@@ -538,10 +549,72 @@ __global__ __launch_bounds__(256) void gemm_splitk_reduce_norm_kernel(const floa
     __syncthreads();
     const float tot = (part[0] + part[1]) + (part[2] + part[3]);
     const float inv = 1.0f / sqrtf(tot / (float)N + eps);
+    typedef unsigned short u16x4_t __attribute__((ext_vector_type(4)));
+    const u16x4_t* grow = (const u16x4_t*)gain;
+    u16x4_t* hrow = (u16x4_t*)(H + (int64_t)m * N);
 #pragma unroll
-    for (int i = 0; i < kMaxPer; ++i) {
+    for (int i = 0; i < kMaxVec; ++i) {
         const int c = tid + i * 256;
-        if (c < N) H[(int64_t)m * N + c] = f32_to_bf16(v[i] * inv * bf16_to_f32(gain[c]));
+        if (c < nvec) {
+            const u16x4_t g = grow[c];
+            u16x4_t o;
+            o.x = f32_to_bf16(v[i].x * inv * bf16_to_f32(bf16{g.x})).bits;
+            o.y = f32_to_bf16(v[i].y * inv * bf16_to_f32(bf16{g.y})).bits;
+            o.z = f32_to_bf16(v[i].z * inv * bf16_to_f32(bf16{g.z})).bits;
+            o.w = f32_to_bf16(v[i].w * inv * bf16_to_f32(bf16{g.w})).bits;
+            hrow[c] = o;
+        }
+    }
+}
+
+// K-split reduction of the QKV projection fused with the rotary embedding and the KV page
+// write: one workgroup per token row sums the partials into LDS (fp32), rotates q and k pairs
+// (i, i + dh/2) by the row's position, stores q back to the activation buffer and k, v into
+// the row's page slot (v transposed).
+__global__ __launch_bounds__(256) void gemm_splitk_reduce_rope_kernel(const float* __restrict__ P, int splits,
+                                                                      int M, int N, RopeKvArgs a) {
+    extern __shared__ float rowsum[];  // [N]
+    const int r = blockIdx.x, tid = threadIdx.x;
+    const int64_t plane = (int64_t)M * N;
+    for (int c = tid; c < N; c += 256) {
+        float acc = 0.f;
+        for (int z = 0; z < splits; ++z) acc += P[z * plane + (int64_t)r * N + c];
+        rowsum[c] = acc;
+    }
+    __syncthreads();
+    bf16* row = (bf16*)a.qkv + (int64_t)r * N;
+    const int dh = a.dh, half = dh / 2;
+    if (a.active && !a.active[r]) {  // finished rollout: keep q defined, append nothing
+        for (int c = tid; c < a.Hq * dh; c += 256) row[c] = f32_to_bf16(rowsum[c]);
+        return;
+    }
+    const int seq = a.row_seq ? a.row_seq[r] : r;
+    const SeqDesc sd = a.seqs[seq];
+    const int pos = sd.pos0 + (r - sd.row_start) + a.pos_add;
+    const int pt = a.geom.page_tokens;
+    const int64_t page = a.tables[sd.table_off + pos / pt];
+    const int slot = pos % pt;
+    bf16* pool = (bf16*)a.kv_pool;
+    const float* cs = a.rope + (int64_t)pos * half * 2;
+    const int n_rot = (a.Hq + a.Hkv) * half;
+    for (int w = tid; w < n_rot; w += 256) {
+        const int head = w / half, i = w % half;
+        const float c = cs[2 * i], s = cs[2 * i + 1];
+        const float x1 = rowsum[head * dh + i], x2 = rowsum[head * dh + i + half];
+        const bf16 y1 = f32_to_bf16(x1 * c - x2 * s), y2 = f32_to_bf16(x2 * c + x1 * s);
+        if (head < a.Hq) {
+            row[head * dh + i] = y1;
+            row[head * dh + i + half] = y2;
+        } else {
+            bf16* kdst = pool + a.geom.k_block(a.layer, page, head - a.Hq) + (int64_t)slot * dh;
+            kdst[i] = y1;
+            kdst[i + half] = y2;
+        }
+    }
+    const int v0 = (a.Hq + a.Hkv) * dh;
+    for (int w = tid; w < a.Hkv * dh; w += 256) {
+        const int kh = w / dh, d = w % dh;
+        pool[a.geom.v_block(a.layer, page, kh) + (int64_t)d * pt + slot] = f32_to_bf16(rowsum[v0 + w]);
     }
 }
 
@@ -595,6 +668,18 @@ int pick_splits(const GemmArgs& a, const TileCfg& t) {
     return splits < 1 ? 1 : splits;
 }
 
+// The fused reduction + rotary kernel keeps one fp32 row in LDS and addresses C with row stride N.
+bool rope_fusable(const GemmArgs& a) {
+    return a.rope && a.epilogue == kEpiStore && a.ldc == a.N && a.N <= 12288 &&
+           a.N == (a.rope->Hq + 2 * a.rope->Hkv) * a.rope->dh;
+}
+
+// The fused reduction + RMSNorm kernel works on 16-byte column groups.
+bool norm_fusable(const GemmArgs& a) {
+    return a.norm_out && a.N <= 8192 && a.N % 4 == 0 && a.ldc % 4 == 0 && ((uintptr_t)a.C % 16 == 0) &&
+           ((uintptr_t)a.norm_out % 8 == 0) && ((uintptr_t)a.norm_gain % 8 == 0);
+}
+
 template <int BM, int BN, int WM, int WN, int EPI, bool SWIGLU>
 hipError_t launch_one(const GemmArgs& a, int splits, void* out, hipStream_t s) {
     // direct-to-LDS pipeline shape: 64-deep slabs in two stages, or 32-deep slabs in four
@@ -646,13 +731,17 @@ hipError_t launch_tile(const GemmArgs& a, int splits, hipStream_t s) {
         const float* P = (const float*)a.ws;
         switch (a.epilogue) {
             case kEpiStore:
+                if (rope_fusable(a)) {
+                    gemm_splitk_reduce_rope_kernel<<<a.M, 256, (size_t)a.N * 4, s>>>(P, splits, a.M, a.N, *a.rope);
+                    return hipGetLastError();
+                }
                 gemm_splitk_reduce_kernel<kEpiStore><<<blocks, 256, 0, s>>>(P, splits, a.M, a.N, a.C, a.ldc);
                 break;
             case kEpiStoreF32:
                 gemm_splitk_reduce_kernel<kEpiStoreF32><<<blocks, 256, 0, s>>>(P, splits, a.M, a.N, a.C, a.ldc);
                 break;
             case kEpiAddF32:
-                if (a.norm_out && a.N <= 8192) {
+                if (norm_fusable(a)) {
                     gemm_splitk_reduce_norm_kernel<<<a.M, 256, 0, s>>>(P, splits, a.M, a.N, (float*)a.C, a.ldc,
                                                                         (const bf16*)a.norm_gain, a.norm_eps,
                                                                         (bf16*)a.norm_out);
@@ -732,16 +821,19 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
     if (a.M <= 0 || a.N <= 0) return hipSuccess;
     const bool want_norm = a.norm_out != nullptr && a.epilogue == kEpiAddF32;
     hipError_t e;
-    bool norm_done = false;
+    bool norm_done = false, rope_done = false;
     if (!mfma_ok(a)) {
         e = a.dtype == kF32 ? launch_generic<float>(a, s) : launch_generic<bf16>(a, s);
     } else {
         const TileCfg t = pick_tile(a);
         const int splits = (a.ws && a.ws_bytes) ? pick_splits(a, t) : 1;
         e = launch_gemm_only(a, splits, t, s);
-        norm_done = want_norm && splits > 1 && a.N <= 8192;  // fused into the K-split reduction
+        norm_done = want_norm && splits > 1 && norm_fusable(a);  // fused into the K-split reduction
+        rope_done = splits > 1 && rope_fusable(a);
     }
-    if (e != hipSuccess || !want_norm || norm_done) return e;
+    if (e != hipSuccess) return e;
+    if (a.rope && a.epilogue == kEpiStore && !rope_done) return launch_rope_kv(*a.rope, s);
+    if (!want_norm || norm_done) return e;
     return launch_rmsnorm((const float*)a.C, nullptr, a.norm_gain, a.dtype, a.N, a.norm_eps, a.norm_out, a.M, s);
 }
 

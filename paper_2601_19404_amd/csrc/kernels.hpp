@@ -26,6 +26,7 @@ enum Epilogue : int {
     kEpiSwiglu = 3,    // W = [gate rows; up rows] (N = 2F): C[M, F] = silu(A Wg^T) * (A Wu^T), input dtype
     kEpiPartial = 4,   // internal: fp32 partial sums of one K split
 };
+struct RopeKvArgs;
 struct GemmArgs {
     const void* A;
     int64_t lda;
@@ -45,6 +46,10 @@ struct GemmArgs {
     const void* norm_gain = nullptr;
     void* norm_out = nullptr;
     float norm_eps = 0.f;
+    // Optional, with kEpiStore only (the QKV projection): after C = A W^T, rotate q and k of every
+    // row and write k, v into the KV pages (rope->qkv must be C).  Fused into the K-split
+    // reduction when the problem is split (the rotation then reads the fp32 sums: one rounding).
+    const RopeKvArgs* rope = nullptr;
 };
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
 

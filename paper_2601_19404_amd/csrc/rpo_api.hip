@@ -383,7 +383,7 @@ struct PassCfg {
 
 hipError_t gemm(rpo_batch* b, const void* A, int64_t lda, const void* W, int64_t ldw, void* C,
                 int64_t ldc, int M, int N, int K, int epi, hipStream_t s, const void* norm_gain = nullptr,
-                void* norm_out = nullptr) {
+                void* norm_out = nullptr, const RopeKvArgs* rope = nullptr) {
     const rpo_model* m = b->m;
     GemmArgs g;
     g.A = A;
@@ -403,6 +403,7 @@ hipError_t gemm(rpo_batch* b, const void* A, int64_t lda, const void* W, int64_t
     g.norm_gain = norm_gain;
     g.norm_out = norm_out;
     g.norm_eps = m->d.rms_eps;
+    g.rope = rope;
     const double es = (double)dtype_size(g.dtype);
     const double out_bytes = epi == kEpiStore ? (double)M * N * es
                              : epi == kEpiStoreF32 ? (double)M * N * 4.0
@@ -427,7 +428,6 @@ hipError_t run_layers(rpo_batch* b, const PassCfg& pc, hipStream_t s) {
     // residual-adding O and down GEMMs write the normalised rows too).
     RET_IF(launch_rmsnorm(x, nullptr, m->attn_norm[0], d.dtype, d.d_model, d.rms_eps, h, pc.rows, s));
     for (int l = 0; l < d.n_layers; ++l) {
-        RET_IF(gemm(b, h, d.d_model, m->wqkv[l], d.d_model, qkv, qw, pc.rows, qw, d.d_model, kEpiStore, s));
         RopeKvArgs ra;
         ra.qkv = qkv;
         ra.dtype = d.dtype;
@@ -444,7 +444,9 @@ hipError_t run_layers(rpo_batch* b, const PassCfg& pc, hipStream_t s) {
         ra.kv_pool = b->kv;
         ra.geom = b->geom;
         ra.layer = l;
-        RET_IF(launch_rope_kv(ra, s));
+        // QKV projection; the rotation + KV page write ride on it (fused when the GEMM is K-split)
+        RET_IF(gemm(b, h, d.d_model, m->wqkv[l], d.d_model, qkv, qw, pc.rows, qw, d.d_model, kEpiStore, s, nullptr,
+                    nullptr, &ra));
         AttnArgs aa;
         aa.q = qkv;
         aa.q_stride = qw;
