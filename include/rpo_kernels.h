@@ -36,7 +36,7 @@ int rpo_gemm_nt(const void *a_dev, int64_t lda, const void *w_dev, int64_t ldw, 
  * 1 = generic vector-ALU kernels for GEMM and attention regardless of shape,
  * 2 = MFMA GEMM with register-staged LDS fills instead of direct-to-LDS loads (the
  *     fallback used when K is not a multiple of 64; selectable for comparison),
- * 16 + k (k = 1..4) = MFMA GEMM with the fixed tile shape of kernel id k (a tuning aid;
+ * 16 + k (k = 1..6) = MFMA GEMM with the fixed tile shape of kernel id k (a tuning aid;
  * attention as in 0).  Not thread-safe against concurrent compute calls.
  * Errors: RPO_EINVAL. */
 int rpo_set_kernel_path(int path);
@@ -50,7 +50,9 @@ int rpo_set_kernel_path(int path);
  * the logits rows read once).  Kernel ids:
  *   1  gemm_mfma_kernel<256,256,2,4,..> (prefill-sized problems and wide decode projections)
  *   2  gemm_mfma_kernel<256,128,2,2,..> (only via rpo_set_kernel_path)
- *   3  gemm_mfma_kernel<128,128,2,2,..> (decode-sized problems)   4  gemm_mfma_kernel<64,128,1,2,..> (M <= 64)
+ *   3  gemm_mfma_kernel<128,128,2,2,..> (decode-sized problems, deep K)   4  gemm_mfma_kernel<64,128,1,2,..> (M <= 64)
+ *   5  gemm_dma_kernel<32,128,1,4,..> (decode QKV projection: rotary embedding and KV page write in the epilogue)
+ *   6  gemm_dma_kernel<64,64,2,2,..> (decode-sized problems, shallow K, no K split)
  *      (all epilogues of a tile shape together; a K-split launch includes its reduction)
  *   7  gemm_generic_kernel      8  attn_decode_mfma_kernel (+ merge)   9  attn_chunk_mfma_kernel
  *   10 sample_kernel

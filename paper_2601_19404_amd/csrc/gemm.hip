@@ -204,11 +204,13 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_kernel(const bf16* __re
     // (i % 8 == x) are mapped to one contiguous run of logical tiles.  Logical tiles are grouped
     // in blocks of blk_m x blk_n = 32 tiles (one per CU of an XCD): the workgroups running
     // together on an XCD then share blk_m row slabs and blk_n weight slabs through its L2.
+    // With at most 8 row tiles the order is plain column-major (blocks of grid_m x 1): no padding
+    // tiles, so a small launch is spread evenly over all XCDs.
     const int per_xcd = (n_tiles + kXcd - 1) / kXcd;
     const int logical = (blockIdx.x % kXcd) * per_xcd + blockIdx.x / kXcd;
     if (logical >= n_tiles) return;
     const int blk_m = grid_m < 8 ? grid_m : 8;
-    const int blk_n = 32 / blk_m;
+    const int blk_n = grid_m <= 8 ? 1 : 4;
     const int blocks_m = (grid_m + blk_m - 1) / blk_m;
     const int blk = logical / (blk_m * blk_n), in_blk = logical % (blk_m * blk_n);
     const int bm = (blk % blocks_m) * blk_m + in_blk % blk_m;
@@ -362,7 +364,8 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const bf16* __res
                                                                const bf16* __restrict__ W, int64_t ldw,
                                                                void* __restrict__ Cv, int64_t ldc, int M,
                                                                int N, int K, int grid_m, int grid_n,
-                                                               int n_tiles, int k_per_split, int F) {
+                                                               int n_tiles, int k_per_split, int F,
+                                                               RopeKvArgs rk) {
     constexpr int NW = WM * WN;
     constexpr int TM = BM / WM, TN = BN / WN;
     constexpr int MI = TM / 32, NI = TN / 32;
@@ -386,7 +389,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const bf16* __res
     const int logical = (blockIdx.x % kXcd) * per_xcd + blockIdx.x / kXcd;
     if (logical >= n_tiles) return;
     const int blk_m = grid_m < 8 ? grid_m : 8;
-    const int blk_n = 32 / blk_m;
+    const int blk_n = grid_m <= 8 ? 1 : 4;
     const int blocks_m = (grid_m + blk_m - 1) / blk_m;
     const int blk = logical / (blk_m * blk_n), in_blk = logical % (blk_m * blk_n);
     const int bm = (blk % blocks_m) * blk_m + in_blk % blk_m;
@@ -473,7 +476,80 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const bf16* __res
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // drain the redundant tail loads before LDS is released
     }
 #undef RPO_DMA_SLAB
-    gemm_epilogue<MI, NI, TM, TN, EPI>(acc, Cv, ldc, M, N, m0, n0, wm, wn, lane);
+    if constexpr (EPI == kEpiRope) {
+        // The tile is BM rows of one head (BN = head_dim = 128, checked by the launcher).  The
+        // accumulators go to LDS as fp32 [BM][BN + 1]; the rotation pairs (i, i + 64) of a row
+        // then sit in one place whatever wave produced them.  q is rotated and stored to C, k is
+        // rotated and stored to its page slot, v is stored transposed into its page.
+        static_assert(EPI != kEpiRope || (BN == 128 && WM == 1 && BM == 32 && NW == 4), "one head per tile");
+        constexpr int LD = BN + 1;
+        float* tile = (float*)smem_raw;
+        int* row_pos = (int*)(tile + BM * LD);   // position, or -1: row beyond M / not active
+        int64_t* row_page = (int64_t*)(row_pos + BM + (BM & 1));
+        __syncthreads();  // every wave's tail loads have landed; the stages can be overwritten
+        {
+            const int col = wn * TN + (lane & 31), row_in = (lane >> 5) * 4;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) tile[(8 * (e >> 2) + row_in + (e & 3)) * LD + col] = acc[0][0][e];
+        }
+        if (tid < BM) {
+            const int r = m0 + tid;
+            int pos = -1;
+            int64_t page = 0;
+            if (r < M && !(rk.active && !rk.active[r])) {
+                const int seq = rk.row_seq ? rk.row_seq[r] : r;
+                const SeqDesc sd = rk.seqs[seq];
+                pos = sd.pos0 + (r - sd.row_start) + rk.pos_add;
+                page = rk.tables[sd.table_off + pos / rk.geom.page_tokens];
+            }
+            row_pos[tid] = pos;
+            row_page[tid] = page;
+        }
+        __syncthreads();
+        const int head = n0 / BN;
+        const int pt = rk.geom.page_tokens;
+        bf16* pool = (bf16*)rk.kv_pool;
+        if (head < rk.Hq + rk.Hkv) {
+            const int i = tid & 63;
+#pragma unroll
+            for (int it = 0; it < BM / 4; ++it) {
+                const int row = it * 4 + (tid >> 6);
+                const int gm = m0 + row;
+                if (gm >= M) continue;
+                const int pos = row_pos[row];
+                const float x1 = tile[row * LD + i], x2 = tile[row * LD + i + 64];
+                bf16* dst;
+                float y1 = x1, y2 = x2;
+                if (pos >= 0) {
+                    const float2 cs = *(const float2*)(rk.rope + ((int64_t)pos * 64 + i) * 2);
+                    y1 = x1 * cs.x - x2 * cs.y;
+                    y2 = x2 * cs.x + x1 * cs.y;
+                }
+                if (head < rk.Hq) {
+                    dst = (bf16*)Cv + (int64_t)gm * ldc + n0;  // a finished rollout keeps an unrotated q
+                } else {
+                    if (pos < 0) continue;
+                    dst = pool + rk.geom.k_block(rk.layer, row_page[row], head - rk.Hq) + (int64_t)(pos % pt) * BN;
+                }
+                dst[i] = f32_to_bf16(y1);
+                dst[i + 64] = f32_to_bf16(y2);
+            }
+        } else {
+            // lanes run over rows: consecutive rows of one sequence fill consecutive slots
+            const int row = tid & 31;
+            const int pos = row_pos[row];
+            if (pos >= 0) {
+                bf16* vdst = pool + rk.geom.v_block(rk.layer, row_page[row], head - rk.Hq - rk.Hkv) + pos % pt;
+#pragma unroll
+                for (int it = 0; it < BN / 8; ++it) {
+                    const int d = it * 8 + (tid >> 5);
+                    vdst[(int64_t)d * pt] = f32_to_bf16(tile[row * LD + d]);
+                }
+            }
+        }
+    } else {
+        gemm_epilogue<MI, NI, TM, TN, EPI>(acc, Cv, ldc, M, N, m0, n0, wm, wn, lane);
+    }
 }
 
 // Sum the K-split partials [splits][M][N] and apply the epilogue.  One thread per output
@@ -637,30 +713,51 @@ bool mfma_ok(const GemmArgs& a) {
     return true;
 }
 
+// The rotary epilogue of the narrow kernel: one head per 128-column tile, rows stored with stride N.
+bool rope_direct(const GemmArgs& a) {
+    return a.rope && a.epilogue == kEpiStore && a.rope->dh == 128 && a.ldc == a.N && a.K % kBK == 0 &&
+           a.N == (a.rope->Hq + 2 * a.rope->Hkv) * 128 && a.path != 2;
+}
+
 TileCfg pick_tile(const GemmArgs& a) {
     if (a.path >= 16) {  // tuning aid: a fixed tile shape
         switch (a.path - 16) {
             case kKidGemm256: return TileCfg{kKidGemm256, 256, 256};
             case kKidGemm256x128: return TileCfg{kKidGemm256x128, 256, 128};
             case kKidGemm128: return TileCfg{kKidGemm128, 128, 128};
+            case kKidGemm32: return TileCfg{kKidGemm32, 32, 128};
+            case kKidGemm64x64: return TileCfg{kKidGemm64x64, 64, 64};
             default: return TileCfg{kKidGemm64, 64, 128};
         }
     }
     // Measured on MI355X: the 8-wave 256x256 tile wins whenever it yields at least ~half a
-    // chip of workgroups; smaller problems do better with 128x128 tiles (two workgroups per
-    // CU) and K splitting.
+    // chip of workgroups.  Smaller problems are bound by what one CU can load per unit time
+    // (every CU has to pull operands): with a shallow K, narrow tiles without K splitting and a
+    // four-deep load pipeline beat wider tiles whose K-split partial sums need a second kernel;
+    // with a deep K, 128x128 tiles split along K.
     const int t256 = ceil_div(a.M, 256) * ceil_div(a.N, 256);
     if (a.M > 512 || (a.M > 64 && t256 >= 128)) return TileCfg{kKidGemm256, 256, 256};
+    if (a.M > 64 && a.K <= 4096 && a.K % kBK == 0 && a.epilogue != kEpiSwiglu && a.path != 2) {
+        if (rope_direct(a)) return TileCfg{kKidGemm32, 32, 128};
+        return TileCfg{kKidGemm64x64, 64, 64};
+    }
     if (a.M > 64) return TileCfg{kKidGemm128, 128, 128};
     return TileCfg{kKidGemm64, 64, 128};
+}
+
+// 128x128 tiles on a deep K run a four-stage pipeline (128 KiB of LDS: one workgroup per CU).
+bool deep_pipeline(const GemmArgs& a, const TileCfg& t) {
+    return t.id == kKidGemm128 && a.K >= 4096 && a.K % kBK == 0 && a.epilogue != kEpiSwiglu && a.path != 2;
 }
 
 // How many K splits: fill the chip (>= ~256 workgroups) without making the slabs per split
 // too few, and only when the workspace can hold the partials.
 int pick_splits(const GemmArgs& a, const TileCfg& t) {
+    if (t.id == kKidGemm32 || t.id == kKidGemm64x64) return 1;
     const int tiles = ceil_div(a.M, t.bm) * ceil_div(a.N, t.bn);
     if (tiles >= 128 || a.K < 1024) return 1;  // half a chip of tiles: splitting costs more than it gains
-    int splits = ceil_div(256, tiles);
+    // one workgroup per CU with the deep pipeline, two otherwise
+    int splits = deep_pipeline(a, t) ? 256 / tiles : ceil_div(256, tiles);
     const int max_by_k = a.K / 512;  // at least 8 slabs per split
     splits = splits < max_by_k ? splits : max_by_k;
     if (splits > 16) splits = 16;
@@ -680,13 +777,12 @@ bool norm_fusable(const GemmArgs& a) {
            ((uintptr_t)a.norm_out % 8 == 0) && ((uintptr_t)a.norm_gain % 8 == 0);
 }
 
-template <int BM, int BN, int WM, int WN, int EPI, bool SWIGLU>
+template <int BM, int BN, int WM, int WN, int EPI, bool SWIGLU, int DST = RPO_DMA_STAGES, int DBK = RPO_DMA_BK>
 hipError_t launch_one(const GemmArgs& a, int splits, void* out, hipStream_t s) {
-    // direct-to-LDS pipeline shape: 64-deep slabs in two stages, or 32-deep slabs in four
-    constexpr int DBK = RPO_DMA_BK, DST = RPO_DMA_STAGES;
+    // direct-to-LDS pipeline shape: DBK-deep slabs in DST stages
     const int gm = ceil_div(a.M, BM), gn = ceil_div(a.N, BN);
     // logical tile space padded to whole blocks of blk_m x blk_n tiles (see the kernel)
-    const int blk_m = gm < 8 ? gm : 8, blk_n = 32 / blk_m;
+    const int blk_m = gm < 8 ? gm : 8, blk_n = gm <= 8 ? 1 : 4;
     const int n_tiles = ceil_div(gm, blk_m) * ceil_div(gn, blk_n) * blk_m * blk_n;
     const int per_xcd = ceil_div(n_tiles, kXcd);
     const int k_per_split = ceil_div(ceil_div(a.K, splits), kBK) * kBK;
@@ -694,9 +790,29 @@ hipError_t launch_one(const GemmArgs& a, int splits, void* out, hipStream_t s) {
     // direct-to-LDS loads need whole 64-deep slabs; path 2 keeps the register-staged kernel
     const bool dma = a.K % kBK == 0 && a.path != 2;
     if (dma) {
-        const size_t lds = (size_t)DST * (BM + BN) * DBK * sizeof(bf16);
+        size_t lds = (size_t)DST * (BM + BN) * DBK * sizeof(bf16);
+        if (EPI == kEpiRope) {  // fp32 tile [BM][BN + 1] + per-row position and page
+            const size_t need = (size_t)BM * (BN + 1) * 4 + (size_t)(BM + (BM & 1)) * 4 + (size_t)BM * 8;
+            lds = lds > need ? lds : need;
+        }
         auto kern = gemm_dma_kernel<BM, BN, WM, WN, EPI, SWIGLU, DBK, DST>;
         static bool attr_set = false;  // one flag per template instance
+        if (!attr_set) {
+            hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+            attr_set = true;
+        }
+        kern<<<grid, block, lds, s>>>((const bf16*)a.A, a.lda, (const bf16*)a.W, a.ldw, out, a.ldc, a.M, a.N, a.K,
+                                      gm, gn, n_tiles, k_per_split, a.N / 2,
+                                      (EPI == kEpiRope && a.rope) ? *a.rope : RopeKvArgs{});
+        return hipGetLastError();
+    }
+    if constexpr (EPI == kEpiRope) {
+        return hipErrorInvalidValue;  // only the direct-to-LDS kernel has this epilogue
+    } else {
+        const size_t lds = (size_t)2 * (BM + BN) * kLdsRow * sizeof(bf16);
+        auto kern = gemm_mfma_kernel<BM, BN, WM, WN, EPI, SWIGLU>;
+        static bool attr_set = false;
         if (!attr_set) {
             hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return e;
@@ -706,25 +822,21 @@ hipError_t launch_one(const GemmArgs& a, int splits, void* out, hipStream_t s) {
                                       gm, gn, n_tiles, k_per_split, a.N / 2);
         return hipGetLastError();
     }
-    const size_t lds = (size_t)2 * (BM + BN) * kLdsRow * sizeof(bf16);
-    auto kern = gemm_mfma_kernel<BM, BN, WM, WN, EPI, SWIGLU>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
-    kern<<<grid, block, lds, s>>>((const bf16*)a.A, a.lda, (const bf16*)a.W, a.ldw, out, a.ldc, a.M, a.N, a.K,
-                                  gm, gn, n_tiles, k_per_split, a.N / 2);
-    return hipGetLastError();
 }
 
-template <int BM, int BN, int WM, int WN>
+template <int BM, int BN, int WM, int WN, int DST = RPO_DMA_STAGES, int DBK = RPO_DMA_BK>
 hipError_t launch_tile(const GemmArgs& a, int splits, hipStream_t s) {
     const bool sw = a.epilogue == kEpiSwiglu;
+    constexpr bool kPairs = (BN / WN / 32) % 2 == 0;  // a wave holds gate/up block pairs
+    if (sw && !kPairs) return hipErrorInvalidValue;
     if (splits > 1) {
-        hipError_t e = sw ? launch_one<BM, BN, WM, WN, kEpiPartial, true>(a, splits, a.ws, s)
-                          : launch_one<BM, BN, WM, WN, kEpiPartial, false>(a, splits, a.ws, s);
+        hipError_t e;
+        if constexpr (kPairs) {
+            e = sw ? launch_one<BM, BN, WM, WN, kEpiPartial, true, DST, DBK>(a, splits, a.ws, s)
+                   : launch_one<BM, BN, WM, WN, kEpiPartial, false, DST, DBK>(a, splits, a.ws, s);
+        } else {
+            e = launch_one<BM, BN, WM, WN, kEpiPartial, false, DST, DBK>(a, splits, a.ws, s);
+        }
         if (e != hipSuccess) return e;
         const int64_t n_out = sw ? (int64_t)a.M * (a.N / 2) : (int64_t)a.M * a.N;
         const unsigned blocks = (unsigned)ceil_div64(n_out, 256);
@@ -757,13 +869,14 @@ hipError_t launch_tile(const GemmArgs& a, int splits, hipStream_t s) {
     }
     switch (a.epilogue) {
         case kEpiStore:
-            return launch_one<BM, BN, WM, WN, kEpiStore, false>(a, 1, a.C, s);
+            return launch_one<BM, BN, WM, WN, kEpiStore, false, DST, DBK>(a, 1, a.C, s);
         case kEpiStoreF32:
-            return launch_one<BM, BN, WM, WN, kEpiStoreF32, false>(a, 1, a.C, s);
+            return launch_one<BM, BN, WM, WN, kEpiStoreF32, false, DST, DBK>(a, 1, a.C, s);
         case kEpiAddF32:
-            return launch_one<BM, BN, WM, WN, kEpiAddF32, false>(a, 1, a.C, s);
+            return launch_one<BM, BN, WM, WN, kEpiAddF32, false, DST, DBK>(a, 1, a.C, s);
         case kEpiSwiglu:
-            return launch_one<BM, BN, WM, WN, kEpiSwiglu, true>(a, 1, a.C, s);
+            if constexpr (kPairs) return launch_one<BM, BN, WM, WN, kEpiSwiglu, true, DST, DBK>(a, 1, a.C, s);
+            return hipErrorInvalidValue;
         default:
             return hipErrorInvalidValue;
     }
@@ -811,7 +924,13 @@ static hipError_t launch_gemm_only(const GemmArgs& a, int splits, const TileCfg&
         case kKidGemm256x128:
             return launch_tile<256, 128, 2, 2>(a, splits, s);
         case kKidGemm128:
+            if (deep_pipeline(a, t)) return launch_tile<128, 128, 2, 2, 4>(a, splits, s);
             return launch_tile<128, 128, 2, 2>(a, splits, s);
+        case kKidGemm32:
+            if (rope_direct(a)) return launch_one<32, 128, 1, 4, kEpiRope, false, 4>(a, 1, a.C, s);
+            return launch_tile<32, 128, 1, 4, 4>(a, splits, s);
+        case kKidGemm64x64:
+            return launch_tile<64, 64, 2, 2, 4>(a, splits, s);
         default:
             return launch_tile<64, 128, 1, 2>(a, splits, s);
     }
@@ -829,7 +948,7 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
         const int splits = (a.ws && a.ws_bytes) ? pick_splits(a, t) : 1;
         e = launch_gemm_only(a, splits, t, s);
         norm_done = want_norm && splits > 1 && norm_fusable(a);  // fused into the K-split reduction
-        rope_done = splits > 1 && rope_fusable(a);
+        rope_done = (splits > 1 && rope_fusable(a)) || (t.id == kKidGemm32 && rope_direct(a));
     }
     if (e != hipSuccess) return e;
     if (a.rope && a.epilogue == kEpiStore && !rope_done) return launch_rope_kv(*a.rope, s);

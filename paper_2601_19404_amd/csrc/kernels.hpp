@@ -25,6 +25,7 @@ enum Epilogue : int {
     kEpiAddF32 = 2,    // C is fp32 and is accumulated into (residual stream)
     kEpiSwiglu = 3,    // W = [gate rows; up rows] (N = 2F): C[M, F] = silu(A Wg^T) * (A Wu^T), input dtype
     kEpiPartial = 4,   // internal: fp32 partial sums of one K split
+    kEpiRope = 5,      // internal: rotary embedding + KV page write from the accumulators (QKV projection)
 };
 struct RopeKvArgs;
 struct GemmArgs {
@@ -60,6 +61,8 @@ enum KernelId : int {
     kKidGemm256x128 = 2,    // gemm_mfma_kernel<256,128,2,2,*> (tuning aid only)
     kKidGemm128 = 3,        // gemm_mfma_kernel<128,128,2,2,*> (decode-sized problems, K split)
     kKidGemm64 = 4,         // gemm_mfma_kernel<64,128,1,2,*>  (M <= 64)
+    kKidGemm32 = 5,         // gemm_dma_kernel<32,128,1,4,*>  (narrow decode projections, no K split)
+    kKidGemm64x64 = 6,      // gemm_dma_kernel<64,64,2,2,*>
     kKidGemmGeneric = 7,
     kKidAttnDecode = 8,     // attn_decode_mfma_kernel
     kKidAttnChunk = 9,      // attn_chunk_mfma_kernel

@@ -64,6 +64,15 @@ def test_gemm_mfma_bf16_model_shapes(rpo, shape, ws_mb):
         _gemm_case(rpo, *shape, torch.bfloat16, epi, path=0, seed=3, ws_mb=ws_mb)
 
 
+@pytest.mark.parametrize("path", [17, 18, 19, 20, 21, 22])
+@pytest.mark.parametrize("shape", [(300, 520, 1536), (77, 1536, 4480)])
+def test_gemm_mfma_bf16_every_tile_shape(rpo, shape, path):
+    """Each tile shape forced in turn (16 + kernel id), with and without a K-split workspace."""
+    for epi in (0, 1, 2):
+        for ws_mb in (0, 64):
+            _gemm_case(rpo, *shape, torch.bfloat16, epi, path=path, seed=5, ws_mb=ws_mb)
+
+
 @pytest.mark.parametrize("path,ws_mb", [(0, 0), (0, 64), (1, 0)])
 @pytest.mark.parametrize("M,F,K", [(512, 8960, 1536), (40, 1024, 768), (700, 256, 2048), (130, 96, 1024)])
 def test_gemm_swiglu(rpo, M, F, K, path, ws_mb):
