@@ -110,40 +110,49 @@ constexpr int kKTile = kPt * kKRow;
 constexpr int kVTile = kDh * kVRow;
 constexpr size_t kAttnLds = (size_t)2 * (kKTile + kVTile) * sizeof(bf16);
 
+// NC = 16-column query tiles per wave: a wave multiplies every K / V fragment it reads from LDS
+// with NC query tiles, so the LDS traffic per flop falls with NC.
+template <int NC>
 struct AttnState {
-    f32x4_t ot[8];  // O^T: lane = query column (lane % 16), rows 16 * mb + 4 * (lane / 16) + i
-    float m, l;     // running max (log2 domain) and this lane's share of the running sum
+    f32x4_t ot[NC][8];  // O^T: lane = query column (lane % 16), rows 16 * mb + 4 * (lane / 16) + i
+    float m[NC], l[NC];  // running max (log2 domain) and this lane's share of the running sum
 };
 
-// Stream pages [page_begin, page_end) of `table` against this lane's query row.
-//   qptr  : the lane's query row (128 bf16) or nullptr for a padding column
-//   limit : tokens visible to the lane's query (absolute count; 0 for padding)
+// Stream pages [page_begin, page_end) of `table` against this lane's NC query rows.
+//   qptr[c]  : the lane's query row (128 bf16) of column tile c, or nullptr for a padding column
+//   limit[c] : tokens visible to that query (absolute count; 0 for padding)
 // Must be called by all 256 threads with the same page range.
-__device__ inline void attn_stream_pages(const bf16* qptr, int limit, const bf16* pool, const KvGeom& geom,
-                                         int layer, int kh, const int32_t* table, int page_begin,
-                                         int page_end, float scale_log2, bf16* smem, bool wave_live,
-                                         AttnState& st) {
+template <int NC>
+__device__ inline void attn_stream_pages(const bf16* const (&qptr)[NC], const int (&limit)[NC], const bf16* pool,
+                                         const KvGeom& geom, int layer, int kh, const int32_t* table,
+                                         int page_begin, int page_end, float scale_log2, bf16* smem,
+                                         bool wave_live, AttnState<NC>& st) {
     const int tid = threadIdx.x, lane = tid & 63;
     const int c16 = lane & 15, g = lane >> 4;
     bf16* Ks = smem;                 // [2][kKTile]
     bf16* Vs = smem + 2 * kKTile;    // [2][kVTile]
 
 #pragma unroll
-    for (int i = 0; i < 8; ++i) st.ot[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    st.m = -INFINITY;
-    st.l = 0.f;
+    for (int c = 0; c < NC; ++c) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) st.ot[c][i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        st.m[c] = -INFINITY;
+        st.l[c] = 0.f;
+    }
     const int np = page_end - page_begin;
     if (np <= 0) return;
 
-    bf16x8_t bq[4];
+    bf16x8_t bq[NC][4];
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-        if (qptr)
-            bq[kk] = *(const bf16x8_t*)(qptr + kk * 32 + 8 * g);
-        else
+    for (int c = 0; c < NC; ++c)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) bq[kk][e] = (__bf16)0.0f;
-    }
+        for (int kk = 0; kk < 4; ++kk) {
+            if (qptr[c])
+                bq[c][kk] = *(const bf16x8_t*)(qptr[c] + kk * 32 + 8 * g);
+            else
+#pragma unroll
+                for (int e = 0; e < 8; ++e) bq[c][kk][e] = (__bf16)0.0f;
+        }
 
     u32x4_t rk[4], rv[4];
     auto load_page = [&](int p) {
@@ -175,61 +184,71 @@ __device__ inline void attn_stream_pages(const bf16* qptr, int limit, const bf16
             const bf16* ks = Ks + buf * kKTile;
             const bf16* vs = Vs + buf * kVTile;
             const int tok0 = (page_begin + p) * kPt;
-            f32x4_t sc[4];
+            f32x4_t sc[NC][4];
 #pragma unroll
             for (int mb = 0; mb < 4; ++mb) {
-                sc[mb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int c = 0; c < NC; ++c) sc[c][mb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int kk = 0; kk < 4; ++kk) {
                     const bf16x8_t ak = *(const bf16x8_t*)(ks + (mb * 16 + c16) * kKRow + kk * 32 + 8 * g);
-                    sc[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ak, bq[kk], sc[mb], 0, 0, 0);
+#pragma unroll
+                    for (int c = 0; c < NC; ++c)
+                        sc[c][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ak, bq[c][kk], sc[c][mb], 0, 0, 0);
                 }
             }
-            float mloc = -INFINITY;
+            bf16x8_t bp[NC][2];
 #pragma unroll
-            for (int mb = 0; mb < 4; ++mb)
+            for (int c = 0; c < NC; ++c) {
+                float mloc = -INFINITY;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const int tok = tok0 + mb * 16 + 4 * g + i;
-                    const float s = (tok < limit) ? sc[mb][i] * scale_log2 : -INFINITY;
-                    sc[mb][i] = s;
-                    mloc = fmaxf(mloc, s);
-                }
-            mloc = fmaxf(mloc, __shfl_xor(mloc, 16, 64));
-            mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
-            const float mnew = fmaxf(st.m, mloc);
-            const float muse = (mnew == -INFINITY) ? 0.f : mnew;
-            const float alpha = exp2f(st.m - muse);
-            float lsum = 0.f;
+                for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
-            for (int mb = 0; mb < 4; ++mb)
+                    for (int i = 0; i < 4; ++i) {
+                        const int tok = tok0 + mb * 16 + 4 * g + i;
+                        const float s = (tok < limit[c]) ? sc[c][mb][i] * scale_log2 : -INFINITY;
+                        sc[c][mb][i] = s;
+                        mloc = fmaxf(mloc, s);
+                    }
+                mloc = fmaxf(mloc, __shfl_xor(mloc, 16, 64));
+                mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+                const float mnew = fmaxf(st.m[c], mloc);
+                const float muse = (mnew == -INFINITY) ? 0.f : mnew;
+                const float alpha = exp2f(st.m[c] - muse);
+                float lsum = 0.f;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const float pv = exp2f(sc[mb][i] - muse);
-                    sc[mb][i] = pv;
-                    lsum += pv;
-                }
-            st.l = st.l * alpha + lsum;
-            st.m = mnew;
+                for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
-            for (int mb2 = 0; mb2 < 8; ++mb2) st.ot[mb2] *= alpha;
+                    for (int i = 0; i < 4; ++i) {
+                        const float pv = exp2f(sc[c][mb][i] - muse);
+                        sc[c][mb][i] = pv;
+                        lsum += pv;
+                    }
+                st.l[c] = st.l[c] * alpha + lsum;
+                st.m[c] = mnew;
 #pragma unroll
-            for (int kk2 = 0; kk2 < 2; ++kk2) {
+                for (int mb2 = 0; mb2 < 8; ++mb2) st.ot[c][mb2] *= alpha;
                 // K slot (g, j) of the second product <-> token 32 kk2 + 4 g + j      (j < 4)
                 //                                     token 32 kk2 + 16 + 4 g + j - 4 (j >= 4)
-                bf16x8_t bp;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    bp[i] = (__bf16)sc[2 * kk2][i];
-                    bp[4 + i] = (__bf16)sc[2 * kk2 + 1][i];
-                }
+                for (int kk2 = 0; kk2 < 2; ++kk2)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        bp[c][kk2][i] = (__bf16)sc[c][2 * kk2][i];
+                        bp[c][kk2][4 + i] = (__bf16)sc[c][2 * kk2 + 1][i];
+                    }
+            }
+#pragma unroll
+            for (int kk2 = 0; kk2 < 2; ++kk2) {
 #pragma unroll
                 for (int mb2 = 0; mb2 < 8; ++mb2) {
                     const bf16* vp = vs + (mb2 * 16 + c16) * kVRow + 32 * kk2 + 4 * g;
                     const bf16x4_t lo = *(const bf16x4_t*)vp;
                     const bf16x4_t hi = *(const bf16x4_t*)(vp + 16);
                     const bf16x8_t av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                    st.ot[mb2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bp, st.ot[mb2], 0, 0, 0);
+#pragma unroll
+                    for (int c = 0; c < NC; ++c)
+                        st.ot[c][mb2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bp[c][kk2], st.ot[c][mb2], 0, 0, 0);
                 }
             }
         }
@@ -237,49 +256,64 @@ __device__ inline void attn_stream_pages(const bf16* qptr, int limit, const bf16
         __syncthreads();
     }
     // every lane of a query column ends with the full row sum
-    st.l += __shfl_xor(st.l, 16, 64);
-    st.l += __shfl_xor(st.l, 32, 64);
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+        st.l[c] += __shfl_xor(st.l[c], 16, 64);
+        st.l[c] += __shfl_xor(st.l[c], 32, 64);
+    }
 }
 
 // ---------------------------------------------------------------------------
 // chunk kernel: grid (q tile, kv head, sequence)
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void attn_chunk_mfma_kernel(AttnArgs a) {
+constexpr int kChunkNC = 2;                  // 16-column query tiles per wave of the chunk kernel
+constexpr int kChunkCols = 64 * kChunkNC;   // query columns (position x head) per workgroup
+
+__global__ __launch_bounds__(256, 2) void attn_chunk_mfma_kernel(AttnArgs a) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     const SeqDesc sd = a.seqs[blockIdx.z];
     const int hpk = a.Hq / a.Hkv;
-    const int ntt = 64 / hpk;  // positions per tile
+    const int ntt = kChunkCols / hpk;  // positions per tile
     const int n_tiles = (sd.n_rows + ntt - 1) / ntt;
     if ((int)blockIdx.x >= n_tiles) return;
     const int qt = n_tiles - 1 - blockIdx.x;  // longest contexts first
     const int kh = blockIdx.y;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int col = wave * 16 + (lane & 15);
-    const int tl = qt * ntt + col / hpk;  // row of the sequence
-    const bool valid = col < ntt * hpk && tl < sd.n_rows;
-    const int head = kh * hpk + col % hpk;
-    const int64_t row = sd.row_start + tl;
-    const bf16* qptr = valid ? (const bf16*)a.q + row * a.q_stride + (int64_t)head * kDh : nullptr;
-    const int limit = valid ? sd.pos0 + tl + a.pos_add + 1 : 0;
+    const bf16* qptr[kChunkNC];
+    int limit[kChunkNC], head[kChunkNC];
+    int64_t row[kChunkNC];
+#pragma unroll
+    for (int c = 0; c < kChunkNC; ++c) {
+        const int col = (wave * kChunkNC + c) * 16 + (lane & 15);
+        const int tl = qt * ntt + col / hpk;  // row of the sequence
+        const bool valid = col < ntt * hpk && tl < sd.n_rows;
+        head[c] = kh * hpk + col % hpk;
+        row[c] = sd.row_start + tl;
+        qptr[c] = valid ? (const bf16*)a.q + row[c] * a.q_stride + (int64_t)head[c] * kDh : nullptr;
+        limit[c] = valid ? sd.pos0 + tl + a.pos_add + 1 : 0;
+    }
     const int last_tl = min(sd.n_rows, (qt + 1) * ntt) - 1;
     const int max_limit = sd.pos0 + last_tl + a.pos_add + 1;
-    const int first_col_of_wave = wave * 16;
+    const int first_col_of_wave = wave * kChunkNC * 16;
     const bool wave_live = first_col_of_wave < ntt * hpk && qt * ntt + first_col_of_wave / hpk < sd.n_rows;
 
-    AttnState st;
-    attn_stream_pages(qptr, limit, (const bf16*)a.kv_pool, a.geom, a.layer, kh, a.tables + sd.table_off, 0,
-                      (max_limit + kPt - 1) / kPt, a.scale * 1.4426950408889634f, (bf16*)smem_raw, wave_live,
-                      st);
-    if (!valid) return;
+    AttnState<kChunkNC> st;
+    attn_stream_pages<kChunkNC>(qptr, limit, (const bf16*)a.kv_pool, a.geom, a.layer, kh, a.tables + sd.table_off, 0,
+                                (max_limit + kPt - 1) / kPt, a.scale * 1.4426950408889634f, (bf16*)smem_raw,
+                                wave_live, st);
     const int g = lane >> 4;
-    const float inv = 1.0f / st.l;
-    bf16* out = (bf16*)a.out + row * (int64_t)a.Hq * kDh + (int64_t)head * kDh;
 #pragma unroll
-    for (int mb2 = 0; mb2 < 8; ++mb2) {
-        bf16x4_t o4;
+    for (int c = 0; c < kChunkNC; ++c) {
+        if (!qptr[c]) continue;
+        const float inv = 1.0f / st.l[c];
+        bf16* out = (bf16*)a.out + row[c] * (int64_t)a.Hq * kDh + (int64_t)head[c] * kDh;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) o4[i] = (__bf16)(st.ot[mb2][i] * inv);
-        *(bf16x4_t*)(out + mb2 * 16 + 4 * g) = o4;
+        for (int mb2 = 0; mb2 < 8; ++mb2) {
+            bf16x4_t o4;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) o4[i] = (__bf16)(st.ot[c][mb2][i] * inv);
+            *(bf16x4_t*)(out + mb2 * 16 + 4 * g) = o4;
+        }
     }
 }
 
@@ -339,21 +373,21 @@ __global__ __launch_bounds__(256) void attn_decode_mfma_kernel(AttnArgs a, Decod
     bool valid = col_ok && row < dg.n_rows;
     if (valid && a.active && !a.active[row]) valid = false;
     const int head = kh * hpk + col % hpk;
-    const bf16* qptr = valid ? (const bf16*)a.q + (int64_t)row * a.q_stride + (int64_t)head * kDh : nullptr;
-    const int limit = valid ? ctx : 0;
+    const bf16* const qptr[1] = {valid ? (const bf16*)a.q + (int64_t)row * a.q_stride + (int64_t)head * kDh : nullptr};
+    const int limit[1] = {valid ? ctx : 0};
 
-    AttnState st;
-    attn_stream_pages(qptr, limit, (const bf16*)a.kv_pool, a.geom, a.layer, kh, a.tables + sd.table_off,
-                      page_begin, page_end, a.scale * 1.4426950408889634f, (bf16*)smem_raw, wave_live, st);
+    AttnState<1> st;
+    attn_stream_pages<1>(qptr, limit, (const bf16*)a.kv_pool, a.geom, a.layer, kh, a.tables + sd.table_off,
+                         page_begin, page_end, a.scale * 1.4426950408889634f, (bf16*)smem_raw, wave_live, st);
     if (!valid) return;
     const int g = lane >> 4;
     const int64_t slot = ((int64_t)row * a.Hq + head) * (dg.n_split + 1) + piece;
     float* po = part_o + slot * kDh;
 #pragma unroll
-    for (int mb2 = 0; mb2 < 8; ++mb2) *(f32x4_t*)(po + mb2 * 16 + 4 * g) = st.ot[mb2];
+    for (int mb2 = 0; mb2 < 8; ++mb2) *(f32x4_t*)(po + mb2 * 16 + 4 * g) = st.ot[0][mb2];
     if (g == 0) {
-        part_ml[2 * slot] = st.m;
-        part_ml[2 * slot + 1] = st.l;
+        part_ml[2 * slot] = st.m[0];
+        part_ml[2 * slot + 1] = st.l[0];
     }
 }
 
@@ -405,7 +439,7 @@ hipError_t launch_attn_chunk(const AttnArgs& a, hipStream_t s) {
     static bool lds_set = false;
     hipError_t e = set_attn_lds((const void*)attn_chunk_mfma_kernel, &lds_set);
     if (e != hipSuccess) return e;
-    const int ntt = 64 / (a.Hq / a.Hkv);
+    const int ntt = kChunkCols / (a.Hq / a.Hkv);
     const dim3 grid(ceil_div(a.max_seq_rows, ntt), a.Hkv, a.n_seqs);
     attn_chunk_mfma_kernel<<<grid, 256, kAttnLds, s>>>(a);
     return hipGetLastError();
