@@ -115,7 +115,7 @@ constexpr size_t kAttnLds = (size_t)2 * (kKTile + kVTile) * sizeof(bf16);
 template <int NC>
 struct AttnState {
     f32x4_t ot[NC][8];  // O^T: lane = query column (lane % 16), rows 16 * mb + 4 * (lane / 16) + i
-    float m[NC], l[NC];  // running max (log2 domain) and this lane's share of the running sum
+    float m[NC], l[NC];  // running max (raw scores inside the loop, log2 domain on return) and this lane's share of the running sum
 };
 
 // Stream pages [page_begin, page_end) of `table` against this lane's NC query rows.
@@ -153,6 +153,14 @@ __device__ inline void attn_stream_pages(const bf16* const (&qptr)[NC], const in
 #pragma unroll
                 for (int e = 0; e < 8; ++e) bq[c][kk][e] = (__bf16)0.0f;
         }
+
+    // smallest visible-token count among this wave's real queries (padding columns never mask)
+    int lim_min = 0x7fffffff;
+#pragma unroll
+    for (int c = 0; c < NC; ++c)
+        if (qptr[c]) lim_min = min(lim_min, limit[c]);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) lim_min = min(lim_min, __shfl_xor(lim_min, o, 64));
 
     u32x4_t rk[4], rv[4];
     auto load_page = [&](int p) {
@@ -198,36 +206,48 @@ __device__ inline void attn_stream_pages(const bf16* const (&qptr)[NC], const in
                 }
             }
             bf16x8_t bp[NC][2];
+            const bool need_mask = tok0 + kPt > lim_min;  // wave-uniform: some query here does not see the whole page
 #pragma unroll
             for (int c = 0; c < NC; ++c) {
+                // online softmax in the raw score domain: p = 2^((s - m) * scale_log2)
                 float mloc = -INFINITY;
+                if (need_mask) {
 #pragma unroll
-                for (int mb = 0; mb < 4; ++mb)
+                    for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const int tok = tok0 + mb * 16 + 4 * g + i;
-                        const float s = (tok < limit[c]) ? sc[c][mb][i] * scale_log2 : -INFINITY;
-                        sc[c][mb][i] = s;
-                        mloc = fmaxf(mloc, s);
-                    }
+                        for (int i = 0; i < 4; ++i) {
+                            const int tok = tok0 + mb * 16 + 4 * g + i;
+                            const float s = (tok < limit[c]) ? sc[c][mb][i] : -INFINITY;
+                            sc[c][mb][i] = s;
+                            mloc = fmaxf(mloc, s);
+                        }
+                } else {
+#pragma unroll
+                    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) mloc = fmaxf(mloc, sc[c][mb][i]);
+                }
                 mloc = fmaxf(mloc, __shfl_xor(mloc, 16, 64));
                 mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
                 const float mnew = fmaxf(st.m[c], mloc);
                 const float muse = (mnew == -INFINITY) ? 0.f : mnew;
-                const float alpha = exp2f(st.m[c] - muse);
+                const float alpha = __builtin_amdgcn_exp2f((st.m[c] - muse) * scale_log2);
+                const float nb = -muse * scale_log2;
                 float lsum = 0.f;
 #pragma unroll
                 for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        const float pv = exp2f(sc[c][mb][i] - muse);
+                        const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[c][mb][i], scale_log2, nb));
                         sc[c][mb][i] = pv;
                         lsum += pv;
                     }
                 st.l[c] = st.l[c] * alpha + lsum;
                 st.m[c] = mnew;
+                if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {  // the running maximum moved in some lane
 #pragma unroll
-                for (int mb2 = 0; mb2 < 8; ++mb2) st.ot[c][mb2] *= alpha;
+                    for (int mb2 = 0; mb2 < 8; ++mb2) st.ot[c][mb2] *= alpha;
+                }
                 // K slot (g, j) of the second product <-> token 32 kk2 + 4 g + j      (j < 4)
                 //                                     token 32 kk2 + 16 + 4 g + j - 4 (j >= 4)
 #pragma unroll
@@ -255,11 +275,12 @@ __device__ inline void attn_stream_pages(const bf16* const (&qptr)[NC], const in
         if (p + 1 < np) store_page(buf ^ 1);
         __syncthreads();
     }
-    // every lane of a query column ends with the full row sum
+    // every lane of a query column ends with the full row sum; the maximum leaves in the log2 domain
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
         st.l[c] += __shfl_xor(st.l[c], 16, 64);
         st.l[c] += __shfl_xor(st.l[c], 32, 64);
+        st.m[c] *= scale_log2;
     }
 }
 
