@@ -105,7 +105,7 @@ __global__ __launch_bounds__(256) void gemm_generic_swiglu_kernel(const T* __res
 // 8 * (e / 4) + 4 * (l / 32) + (e % 4) of each 32x32 block.
 template <int MI, int NI, int TM, int TN, int EPI>
 __device__ inline void gemm_epilogue(f32x16_t (&acc)[MI][NI], void* __restrict__ Cv, int64_t ldc, int M, int N,
-                                     int m0, int n0, int wm, int wn, int lane) {
+                                     int m0, int n0, int wm, int wn, int lane, int split) {
     const int col_in = lane & 31, row_in = (lane >> 5) * 4;
     if (EPI == kEpiSwiglu) {
         // blocks (j, j + 1) = (gate, up) of output columns (n0 + wn*TN)/2 + (j/2)*32 + col_in
@@ -126,7 +126,7 @@ __device__ inline void gemm_epilogue(f32x16_t (&acc)[MI][NI], void* __restrict__
             }
         return;
     }
-    float* Cp = (float*)Cv + (EPI == kEpiPartial ? (int64_t)blockIdx.y * M * (int64_t)N : 0);
+    float* Cp = (float*)Cv + (EPI == kEpiPartial ? (int64_t)split * M * (int64_t)N : 0);
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
 #pragma unroll
@@ -180,14 +180,44 @@ __device__ inline int weight_row(int n, int F) {
     return ((n >> 5) & 1) * F + ((n >> 6) << 5) + (n & 31);
 }
 
+// Tile order shared by the MFMA kernels.  A launch has n_tiles * splits work items (item =
+// split * n_tiles + logical tile).  Workgroup ids are dealt round-robin to the 8 XCDs, so the ids one
+// XCD sees (i % 8 == x) are mapped to one contiguous run of items, the runs as equal as possible:
+// a launch of about one workgroup per CU then really puts one on every CU.  Logical tiles are
+// grouped in blocks of blk_m x blk_n = 32 tiles (one per CU of an XCD): the workgroups running
+// together on an XCD share blk_m row slabs and blk_n weight slabs through its L2.  With at most 8
+// row tiles the order is plain column-major (blocks of grid_m x 1): no padding tiles.
+struct TileCoord {
+    int bm, bn, split;
+    bool ok;
+};
+__device__ inline TileCoord tile_coord(int n_tiles, int splits, int grid_m, int grid_n) {
+    TileCoord t{0, 0, 0, false};
+    const int total = n_tiles * splits;
+    const int xcd = blockIdx.x % kXcd;
+    const int start = (int)(((int64_t)xcd * total) / kXcd), next = (int)(((int64_t)(xcd + 1) * total) / kXcd);
+    const int item = start + blockIdx.x / kXcd;
+    if (item >= next) return t;
+    t.split = item / n_tiles;
+    const int logical = item % n_tiles;
+    const int blk_m = grid_m < 8 ? grid_m : 8;
+    const int blk_n = grid_m <= 8 ? 1 : 4;
+    const int blocks_m = (grid_m + blk_m - 1) / blk_m;
+    const int blk = logical / (blk_m * blk_n), in_blk = logical % (blk_m * blk_n);
+    t.bm = (blk % blocks_m) * blk_m + in_blk % blk_m;
+    t.bn = (blk / blocks_m) * blk_n + in_blk / blk_m;
+    t.ok = t.bm < grid_m && t.bn < grid_n;
+    return t;
+}
+
 // EPI: kEpiStore / kEpiStoreF32 / kEpiAddF32 / kEpiSwiglu write the result; kEpiPartial writes
-// fp32 partial sums of K-split `blockIdx.y` to Cv[split][M][N].
+// fp32 partial sums of its K split to Cv[split][M][N].
 template <int BM, int BN, int WM, int WN, int EPI, bool SWIGLU>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_kernel(const bf16* __restrict__ A, int64_t lda,
                                                                 const bf16* __restrict__ W, int64_t ldw,
                                                                 void* __restrict__ Cv, int64_t ldc,
                                                                 int M, int N, int K, int grid_m, int grid_n,
-                                                                int n_tiles, int k_per_split, int F) {
+                                                                int n_tiles, int splits, int k_per_split, int F) {
     constexpr int NT = WM * WN * 64;
     constexpr int TM = BM / WM, TN = BN / WN;
     constexpr int MI = TM / 32, NI = TN / 32;
@@ -200,26 +230,12 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_kernel(const bf16* __re
     bf16* As = (bf16*)smem_raw;                 // [2][BM][kLdsRow]
     bf16* Bs = As + 2 * BM * kLdsRow;           // [2][BN][kLdsRow]
 
-    // Tile order.  Workgroup ids are dealt round-robin to the 8 XCDs, so the ids one XCD sees
-    // (i % 8 == x) are mapped to one contiguous run of logical tiles.  Logical tiles are grouped
-    // in blocks of blk_m x blk_n = 32 tiles (one per CU of an XCD): the workgroups running
-    // together on an XCD then share blk_m row slabs and blk_n weight slabs through its L2.
-    // With at most 8 row tiles the order is plain column-major (blocks of grid_m x 1): no padding
-    // tiles, so a small launch is spread evenly over all XCDs.
-    const int per_xcd = (n_tiles + kXcd - 1) / kXcd;
-    const int logical = (blockIdx.x % kXcd) * per_xcd + blockIdx.x / kXcd;
-    if (logical >= n_tiles) return;
-    const int blk_m = grid_m < 8 ? grid_m : 8;
-    const int blk_n = grid_m <= 8 ? 1 : 4;
-    const int blocks_m = (grid_m + blk_m - 1) / blk_m;
-    const int blk = logical / (blk_m * blk_n), in_blk = logical % (blk_m * blk_n);
-    const int bm = (blk % blocks_m) * blk_m + in_blk % blk_m;
-    const int bn = (blk / blocks_m) * blk_n + in_blk / blk_m;
-    if (bm >= grid_m || bn >= grid_n) return;
-    const int m0 = bm * BM, n0 = bn * BN;
+    const TileCoord tc = tile_coord(n_tiles, splits, grid_m, grid_n);
+    if (!tc.ok) return;
+    const int m0 = tc.bm * BM, n0 = tc.bn * BN;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave % WM, wn = wave / WM;
-    const int k_begin = blockIdx.y * k_per_split;
+    const int k_begin = tc.split * k_per_split;
     const int k_end = min(K, k_begin + k_per_split);
 
     // Thread t moves the 16-byte piece (row t / 8 + i * NT / 8, k-chunk t % 8) of each slab.
@@ -323,7 +339,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_kernel(const bf16* __re
 #undef RPO_STORE_SLAB
 #undef RPO_MULTIPLY_SLAB
 
-    gemm_epilogue<MI, NI, TM, TN, EPI>(acc, Cv, ldc, M, N, m0, n0, wm, wn, lane);
+    gemm_epilogue<MI, NI, TM, TN, EPI>(acc, Cv, ldc, M, N, m0, n0, wm, wn, lane, tc.split);
 }
 
 // ---------------------------------------------------------------------------
@@ -364,7 +380,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const bf16* __res
                                                                const bf16* __restrict__ W, int64_t ldw,
                                                                void* __restrict__ Cv, int64_t ldc, int M,
                                                                int N, int K, int grid_m, int grid_n,
-                                                               int n_tiles, int k_per_split, int F,
+                                                               int n_tiles, int splits, int k_per_split, int F,
                                                                RopeKvArgs rk) {
     constexpr int NW = WM * WN;
     constexpr int TM = BM / WM, TN = BN / WN;
@@ -385,21 +401,13 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const bf16* __res
     const uint32_t lds_a = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem_raw;
     const uint32_t lds_b = lds_a + STAGES * A_STAGE * 2;
 
-    const int per_xcd = (n_tiles + kXcd - 1) / kXcd;
-    const int logical = (blockIdx.x % kXcd) * per_xcd + blockIdx.x / kXcd;
-    if (logical >= n_tiles) return;
-    const int blk_m = grid_m < 8 ? grid_m : 8;
-    const int blk_n = grid_m <= 8 ? 1 : 4;
-    const int blocks_m = (grid_m + blk_m - 1) / blk_m;
-    const int blk = logical / (blk_m * blk_n), in_blk = logical % (blk_m * blk_n);
-    const int bm = (blk % blocks_m) * blk_m + in_blk % blk_m;
-    const int bn = (blk / blocks_m) * blk_n + in_blk / blk_m;
-    if (bm >= grid_m || bn >= grid_n) return;
-    const int m0 = bm * BM, n0 = bn * BN;
+    const TileCoord tc = tile_coord(n_tiles, splits, grid_m, grid_n);
+    if (!tc.ok) return;
+    const int m0 = tc.bm * BM, n0 = tc.bn * BN;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave % WM, wn = wave / WM;
-    const int k_begin = blockIdx.y * k_per_split;
+    const int k_begin = tc.split * k_per_split;
     const int k_end = min(K, k_begin + k_per_split);
     const int nk = (k_end - k_begin) / BK;
 
@@ -548,7 +556,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const bf16* __res
             }
         }
     } else {
-        gemm_epilogue<MI, NI, TM, TN, EPI>(acc, Cv, ldc, M, N, m0, n0, wm, wn, lane);
+        gemm_epilogue<MI, NI, TM, TN, EPI>(acc, Cv, ldc, M, N, m0, n0, wm, wn, lane, tc.split);
     }
 }
 
@@ -784,9 +792,9 @@ hipError_t launch_one(const GemmArgs& a, int splits, void* out, hipStream_t s) {
     // logical tile space padded to whole blocks of blk_m x blk_n tiles (see the kernel)
     const int blk_m = gm < 8 ? gm : 8, blk_n = gm <= 8 ? 1 : 4;
     const int n_tiles = ceil_div(gm, blk_m) * ceil_div(gn, blk_n) * blk_m * blk_n;
-    const int per_xcd = ceil_div(n_tiles, kXcd);
+    const int per_xcd = ceil_div(n_tiles * splits, kXcd);  // work items (tile, split) per XCD
     const int k_per_split = ceil_div(ceil_div(a.K, splits), kBK) * kBK;
-    const dim3 grid((unsigned)(per_xcd * kXcd), (unsigned)splits), block(WM * WN * 64);
+    const dim3 grid((unsigned)(per_xcd * kXcd)), block(WM * WN * 64);
     // direct-to-LDS loads need whole 64-deep slabs; path 2 keeps the register-staged kernel
     const bool dma = a.K % kBK == 0 && a.path != 2;
     if (dma) {
@@ -803,7 +811,7 @@ hipError_t launch_one(const GemmArgs& a, int splits, void* out, hipStream_t s) {
             attr_set = true;
         }
         kern<<<grid, block, lds, s>>>((const bf16*)a.A, a.lda, (const bf16*)a.W, a.ldw, out, a.ldc, a.M, a.N, a.K,
-                                      gm, gn, n_tiles, k_per_split, a.N / 2,
+                                      gm, gn, n_tiles, splits, k_per_split, a.N / 2,
                                       (EPI == kEpiRope && a.rope) ? *a.rope : RopeKvArgs{});
         return hipGetLastError();
     }
@@ -819,7 +827,7 @@ hipError_t launch_one(const GemmArgs& a, int splits, void* out, hipStream_t s) {
             attr_set = true;
         }
         kern<<<grid, block, lds, s>>>((const bf16*)a.A, a.lda, (const bf16*)a.W, a.ldw, out, a.ldc, a.M, a.N, a.K,
-                                      gm, gn, n_tiles, k_per_split, a.N / 2);
+                                      gm, gn, n_tiles, splits, k_per_split, a.N / 2);
         return hipGetLastError();
     }
 }
