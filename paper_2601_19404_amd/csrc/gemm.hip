@@ -745,7 +745,7 @@ TileCfg pick_tile(const GemmArgs& a) {
     // with a deep K, 128x128 tiles split along K.
     const int t256 = ceil_div(a.M, 256) * ceil_div(a.N, 256);
     if (a.M > 512 || (a.M > 64 && t256 >= 128)) return TileCfg{kKidGemm256, 256, 256};
-    if (a.M > 64 && a.K <= 4096 && a.K % kBK == 0 && a.epilogue != kEpiSwiglu && a.path != 2) {
+    if (a.K <= 4096 && a.K % kBK == 0 && a.epilogue != kEpiSwiglu && a.path != 2) {
         if (rope_direct(a)) return TileCfg{kKidGemm32, 32, 128};
         return TileCfg{kKidGemm64x64, 64, 64};
     }
@@ -753,9 +753,13 @@ TileCfg pick_tile(const GemmArgs& a) {
     return TileCfg{kKidGemm64, 64, 128};
 }
 
-// 128x128 tiles on a deep K run a four-stage pipeline (128 KiB of LDS: one workgroup per CU).
+// 128x128 and 64x128 tiles run a four-stage pipeline (128 / 96 KiB of LDS: one workgroup per CU)
+// when the launch has at most one workgroup per CU anyway: operands that come from HBM need the
+// deeper prefetch.  A deep K is split so that this holds.
 bool deep_pipeline(const GemmArgs& a, const TileCfg& t) {
-    return t.id == kKidGemm128 && a.K >= 4096 && a.K % kBK == 0 && a.epilogue != kEpiSwiglu && a.path != 2;
+    if ((t.id != kKidGemm128 && t.id != kKidGemm64) || a.K % kBK != 0 || a.path == 2) return false;
+    const int tiles = ceil_div(a.M, t.bm) * ceil_div(a.N, t.bn);
+    return tiles <= 256 && (a.K >= 4096 || tiles >= 128 || a.ws == nullptr);
 }
 
 // How many K splits: fill the chip (>= ~256 workgroups) without making the slabs per split
@@ -940,6 +944,7 @@ static hipError_t launch_gemm_only(const GemmArgs& a, int splits, const TileCfg&
         case kKidGemm64x64:
             return launch_tile<64, 64, 2, 2, 4>(a, splits, s);
         default:
+            if (deep_pipeline(a, t)) return launch_tile<64, 128, 1, 2, 4>(a, splits, s);
             return launch_tile<64, 128, 1, 2>(a, splits, s);
     }
 }
