@@ -36,7 +36,7 @@ int rpo_gemm_nt(const void *a_dev, int64_t lda, const void *w_dev, int64_t ldw, 
  * 1 = generic vector-ALU kernels for GEMM and attention regardless of shape,
  * 2 = MFMA GEMM with register-staged LDS fills instead of direct-to-LDS loads (the
  *     fallback used when K is not a multiple of 64; selectable for comparison),
- * 16 + k (k = 1..6) = MFMA GEMM with the fixed tile shape of kernel id k (a tuning aid;
+ * 16 + k (k = 1..6, 11) = MFMA GEMM with the fixed tile shape of kernel id k (a tuning aid;
  * attention as in 0).  Not thread-safe against concurrent compute calls.
  * Errors: RPO_EINVAL. */
 int rpo_set_kernel_path(int path);
@@ -54,6 +54,7 @@ int rpo_set_kernel_path(int path);
  *   5  gemm_dma_kernel<32,128,1,4,..> (decode QKV projection: rotary embedding and KV page write in the epilogue)
  *   6  gemm_dma_kernel<64,64,2,2,..> (decode-sized problems, shallow K, no K split)
  *      (all epilogues of a tile shape together; a K-split launch includes its reduction)
+ *   11 gemm_dma_kernel<256,192,4,2,..> (large M with a narrow N: fewer idle CUs in the last round of workgroups)
  *   7  gemm_generic_kernel      8  attn_decode_mfma_kernel (+ merge)   9  attn_chunk_mfma_kernel
  *   10 sample_kernel
  * Host-side only (event create / record / synchronise); not thread-safe.

@@ -316,7 +316,7 @@ def rpo_last_error() -> str:
     return lib().rpo_last_error().decode()
 
 
-KERNEL_IDS = {"gemm256": 1, "gemm256x128": 2, "gemm128": 3, "gemm64": 4, "gemm32": 5, "gemm64x64": 6, "gemm_generic": 7,
+KERNEL_IDS = {"gemm256": 1, "gemm256x128": 2, "gemm128": 3, "gemm64": 4, "gemm32": 5, "gemm64x64": 6, "gemm_generic": 7, "gemm256x192": 11,
               "attn_decode": 8, "attn_chunk": 9, "sample": 10}
 
 

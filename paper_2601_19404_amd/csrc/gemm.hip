@@ -735,6 +735,9 @@ TileCfg pick_tile(const GemmArgs& a) {
             case kKidGemm128: return TileCfg{kKidGemm128, 128, 128};
             case kKidGemm32: return TileCfg{kKidGemm32, 32, 128};
             case kKidGemm64x64: return TileCfg{kKidGemm64x64, 64, 64};
+            case kKidGemm256x192:  // no fused gate/up epilogue for this shape
+                if (a.epilogue != kEpiSwiglu) return TileCfg{kKidGemm256x192, 256, 192};
+                return TileCfg{kKidGemm256, 256, 256};
             default: return TileCfg{kKidGemm64, 64, 128};
         }
     }
@@ -744,7 +747,15 @@ TileCfg pick_tile(const GemmArgs& a) {
     // four-deep load pipeline beat wider tiles whose K-split partial sums need a second kernel;
     // with a deep K, 128x128 tiles split along K.
     const int t256 = ceil_div(a.M, 256) * ceil_div(a.N, 256);
-    if (a.M > 512 || (a.M > 64 && t256 >= 128)) return TileCfg{kKidGemm256, 256, 256};
+    if (a.M > 512 || (a.M > 64 && t256 >= 128)) {
+        // Workgroups run in rounds of one per CU.  A 256x192 tile costs about 0.78 of a 256x256
+        // one; it wins when the wider tile would leave much of its last round idle (narrow N).
+        if (a.epilogue != kEpiSwiglu && a.M > 512) {
+            const int t192 = ceil_div(a.M, 256) * ceil_div(a.N, 192);
+            if (ceil_div(t192, 256) * 0.78 < ceil_div(t256, 256) * 0.97) return TileCfg{kKidGemm256x192, 256, 192};
+        }
+        return TileCfg{kKidGemm256, 256, 256};
+    }
     if (a.K <= 4096 && a.K % kBK == 0 && a.epilogue != kEpiSwiglu && a.path != 2) {
         if (rope_direct(a)) return TileCfg{kKidGemm32, 32, 128};
         return TileCfg{kKidGemm64x64, 64, 64};
@@ -943,6 +954,8 @@ static hipError_t launch_gemm_only(const GemmArgs& a, int splits, const TileCfg&
             return launch_tile<32, 128, 1, 4, 4>(a, splits, s);
         case kKidGemm64x64:
             return launch_tile<64, 64, 2, 2, 4>(a, splits, s);
+        case kKidGemm256x192:
+            return launch_tile<256, 192, 4, 2>(a, splits, s);
         default:
             if (deep_pipeline(a, t)) return launch_tile<64, 128, 1, 2, 4>(a, splits, s);
             return launch_tile<64, 128, 1, 2>(a, splits, s);

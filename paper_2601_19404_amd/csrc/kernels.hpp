@@ -64,10 +64,11 @@ enum KernelId : int {
     kKidGemm32 = 5,         // gemm_dma_kernel<32,128,1,4,*>  (narrow decode projections, no K split)
     kKidGemm64x64 = 6,      // gemm_dma_kernel<64,64,2,2,*>
     kKidGemmGeneric = 7,
+    kKidGemm256x192 = 11,   // gemm_dma_kernel<256,192,4,2,*> (large M, narrow N: fewer idle CUs in the last round)
     kKidAttnDecode = 8,     // attn_decode_mfma_kernel
     kKidAttnChunk = 9,      // attn_chunk_mfma_kernel
     kKidSample = 10,        // sample_kernel
-    kKidCount = 11,
+    kKidCount = 12,
 };
 // Which kernel launch_gemm picks for these arguments.
 int gemm_kernel_id(const GemmArgs& a);

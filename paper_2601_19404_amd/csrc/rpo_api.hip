@@ -40,8 +40,8 @@ static int fail(int code, const char* fmt, ...) {
 extern "C" const char* rpo_last_error(void) { return g_err; }
 
 extern "C" int rpo_set_kernel_path(int path) {
-    if (path != 0 && path != 1 && path != 2 && !(path >= 17 && path <= 22))
-        return fail(RPO_EINVAL, "kernel path must be 0, 1, 2 or 17..22");
+    if (path != 0 && path != 1 && path != 2 && !(path >= 17 && path <= 22) && path != 27)
+        return fail(RPO_EINVAL, "kernel path must be 0, 1, 2, 17..22 or 27");
     g_kernel_path = path;
     return RPO_OK;
 }

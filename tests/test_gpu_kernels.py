@@ -56,7 +56,7 @@ def test_gemm_mfma_bf16(rpo, shape, epi):
 
 
 @pytest.mark.parametrize("ws_mb", [0, 64])
-@pytest.mark.parametrize("shape", [(512, 2048, 1536), (64, 4096, 1536), (200, 1536, 8960), (1000, 640, 1536),
+@pytest.mark.parametrize("shape", [(512, 2048, 1536), (64, 4096, 1536), (200, 1536, 8960), (1000, 640, 1536), (2100, 1536, 512),
                                    (504, 1536, 8960), (8, 1536, 8960)])
 def test_gemm_mfma_bf16_model_shapes(rpo, shape, ws_mb):
     """Every tile shape (256x256, 256x128, 128x128, 64x128), with and without K splitting."""
@@ -64,7 +64,7 @@ def test_gemm_mfma_bf16_model_shapes(rpo, shape, ws_mb):
         _gemm_case(rpo, *shape, torch.bfloat16, epi, path=0, seed=3, ws_mb=ws_mb)
 
 
-@pytest.mark.parametrize("path", [17, 18, 19, 20, 21, 22])
+@pytest.mark.parametrize("path", [17, 18, 19, 20, 21, 22, 27])
 @pytest.mark.parametrize("shape", [(300, 520, 1536), (77, 1536, 4480)])
 def test_gemm_mfma_bf16_every_tile_shape(rpo, shape, path):
     """Each tile shape forced in turn (16 + kernel id), with and without a K-split workspace."""
