@@ -464,19 +464,34 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const bf16* __res
             RPO_DMA_SLAB(kt + STAGES - 1);  // into the stage whose slab (kt - 1) everyone has finished reading
             const bf16* as = As + stage * A_STAGE + (wm * TM + frag_row) * BK;
             const bf16* bs = Bs + stage * B_STAGE + (wn * TN + frag_row) * BK;
+            // Fragments are double-buffered in registers: the LDS reads of k-step ks + 1 are issued
+            // before the MFMAs of k-step ks, so the LDS pipe and the matrix pipe work at the same time.
+            constexpr int KS = BK / 16;
+            bf16x8_t af[2][MI], bfr[2][NI];
+            {
+                const int piece = (frag_half ^ frag_g) * 8;
 #pragma unroll
-            for (int ks = 0; ks < BK / 16; ++ks) {
-                const int piece = ((ks * 2 + frag_half) ^ frag_g) * 8;
-                bf16x8_t af[MI], bfr[NI];
+                for (int i = 0; i < MI; ++i) af[0][i] = *(const bf16x8_t*)(as + i * 32 * BK + piece);
 #pragma unroll
-                for (int i = 0; i < MI; ++i) af[i] = *(const bf16x8_t*)(as + i * 32 * BK + piece);
+                for (int j = 0; j < NI; ++j) bfr[0][j] = *(const bf16x8_t*)(bs + j * 32 * BK + piece);
+            }
 #pragma unroll
-                for (int j = 0; j < NI; ++j) bfr[j] = *(const bf16x8_t*)(bs + j * 32 * BK + piece);
+            for (int ks = 0; ks < KS; ++ks) {
+                const int cur = ks & 1, nxt = cur ^ 1;
+                if (ks + 1 < KS) {
+                    const int piece = (((ks + 1) * 2 + frag_half) ^ frag_g) * 8;
+#pragma unroll
+                    for (int i = 0; i < MI; ++i) af[nxt][i] = *(const bf16x8_t*)(as + i * 32 * BK + piece);
+#pragma unroll
+                    for (int j = 0; j < NI; ++j) bfr[nxt][j] = *(const bf16x8_t*)(bs + j * 32 * BK + piece);
+                }
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int i = 0; i < MI; ++i)
 #pragma unroll
                     for (int j = 0; j < NI; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][i], bfr[cur][j], acc[i][j], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
             }
             asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kInFlight) : "memory");
             __syncthreads();
