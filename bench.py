@@ -321,6 +321,17 @@ def main():
                                peak_GBps=8000.0,
                                frac=algorithmic_decode_bytes(st) / 1e9 / (phases.get("decode", float("nan")) / 1e3) / 8000.0),
                roofline=roofline)
+    # what this GPU sustains on a plain copy and on an MFMA issue loop, measured now (outside the
+    # timed region): context for the fractions above, which are against the published peaks
+    try:
+        copy_gbps, mfma_tflops = rpo.rpo_probe_peaks()
+        out["practical_peaks"] = dict(copy_GBps=round(copy_gbps, 1), mfma_bf16_TFLOPs=round(mfma_tflops, 1),
+                                      note="plain copy (read + write) and bf16 32x32x16 MFMA issue loop, "
+                                           "measured by rpo_probe_peaks in this run")
+        practical = mfma_tflops if bound == "mfma" else copy_gbps
+        roofline["frac_of_practical"] = achieved / practical if practical > 0 else None
+    except rpo.RpoError as e:  # the probe is informational
+        out["practical_peaks"] = dict(error=str(e))
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(st)
     print(json.dumps(out), flush=True)

@@ -32,6 +32,17 @@ int rpo_gemm_nt(const void *a_dev, int64_t lda, const void *w_dev, int64_t ldw, 
                 int32_t M, int32_t N, int32_t K, int32_t dtype, int32_t epilogue, void *ws_dev,
                 size_t ws_bytes, void *stream);
 
+/* Practical ceilings of the GPU the library runs on, for roofline reports: the rate of a plain
+ * device-to-device copy of `bytes` bytes (read + write counted, GB/s, best of three launches) and
+ * of a back-to-back bf16 32x32x16 MFMA issue loop with changing operands (TFLOP/s, two workgroups
+ * of four waves per CU, about 0.1 s, best of two).
+ *   src_dev, dst_dev  device, `bytes` long each (a multiple of 16, at least 1 MiB), not overlapping
+ *   scratch_dev       device, 512 * 256 floats, overwritten
+ *   copy_gbps, mfma_tflops  host, results
+ * Synchronises the stream.  Errors: RPO_EINVAL, RPO_EHIP. */
+int rpo_probe_peaks(const void *src_dev, void *dst_dev, size_t bytes, float *scratch_dev, double *copy_gbps,
+                    double *mfma_tflops, void *stream);
+
 /* Process-wide kernel selection: 0 = fastest available kernel for the shape (default),
  * 1 = generic vector-ALU kernels for GEMM and attention regardless of shape,
  * 2 = MFMA GEMM with register-staged LDS fills instead of direct-to-LDS loads (the

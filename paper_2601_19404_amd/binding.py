@@ -73,13 +73,14 @@ def lib() -> C.CDLL:
     L.rpo_objective_forward.argtypes = [vp, vp, vp, vp, vp, i32, i32, f32, f32, vp, vp, vp, vp]
     L.rpo_shape_rewards.argtypes = [vp, vp, i32, i32, f32, f32, f32, vp, vp]
     L.rpo_gemm_nt.argtypes = [vp, i64, vp, i64, vp, i64, i32, i32, i32, i32, i32, vp, sz, vp]
+    L.rpo_probe_peaks.argtypes = [vp, vp, sz, vp, C.POINTER(C.c_double), C.POINTER(C.c_double), vp]
     L.rpo_set_kernel_path.argtypes = [C.c_int]
     L.rpo_profile_start.argtypes = [C.c_int]
     L.rpo_profile_stop.argtypes = [C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double),
                                    C.POINTER(C.c_double)]
     for name in ("rpo_model_create", "rpo_batch_create", "rpo_prefill_prefix", "rpo_kv_fork",
                  "rpo_decode_step", "rpo_sample", "rpo_suffix_logprobs", "grpo_advantages",
-                 "rpo_shape_rewards", "rpo_objective_forward", "rpo_gemm_nt", "rpo_set_kernel_path", "rpo_profile_start", "rpo_profile_stop"):
+                 "rpo_shape_rewards", "rpo_objective_forward", "rpo_gemm_nt", "rpo_set_kernel_path", "rpo_profile_start", "rpo_profile_stop", "rpo_probe_peaks"):
         getattr(L, name).restype = C.c_int
     _lib = L
     return L
@@ -89,7 +90,7 @@ EXPORTS = ("rpo_model_create", "rpo_model_destroy", "rpo_kv_pool_bytes", "rpo_wo
            "rpo_batch_create", "rpo_batch_destroy", "rpo_prefill_prefix", "rpo_kv_fork",
            "rpo_decode_step", "rpo_sample", "rpo_suffix_logprobs", "grpo_advantages",
            "rpo_shape_rewards", "rpo_objective_forward", "rpo_last_error", "rpo_gemm_nt", "rpo_set_kernel_path", "rpo_profile_start",
-           "rpo_profile_stop")
+           "rpo_profile_stop", "rpo_probe_peaks")
 
 
 def _check(code: int) -> None:
@@ -314,6 +315,17 @@ def rpo_set_kernel_path(path: int) -> None:
 
 def rpo_last_error() -> str:
     return lib().rpo_last_error().decode()
+
+
+def rpo_probe_peaks(n_bytes: int = 1 << 30, stream=None):
+    """(copy GB/s counting read + write, bf16 MFMA issue-loop TFLOP/s) of the current GPU."""
+    src = torch.ones(n_bytes // 4, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    scratch = torch.empty(512 * 256, dtype=torch.float32, device="cuda")
+    gbps, tflops = C.c_double(0.0), C.c_double(0.0)
+    _check(lib().rpo_probe_peaks(_ptr(src), _ptr(dst), C.c_size_t(n_bytes), _ptr(scratch), C.byref(gbps),
+                                 C.byref(tflops), _stream(stream)))
+    return gbps.value, tflops.value
 
 
 KERNEL_IDS = {"gemm256": 1, "gemm256x128": 2, "gemm128": 3, "gemm64": 4, "gemm32": 5, "gemm64x64": 6, "gemm_generic": 7, "gemm256x192": 11,

@@ -54,6 +54,10 @@ struct GemmArgs {
 };
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
 
+// Practical-ceiling probes (probes.hip): a plain copy (GB/s, read + write) and an MFMA issue loop.
+hipError_t probe_copy(const void* src, void* dst, size_t bytes, int reps, double* gbps, hipStream_t s);
+hipError_t probe_mfma(float* scratch, int iters, int reps, double* tflops, hipStream_t s);
+
 // Identifiers of the kernels whose launches can be timed (rpo_profile_start).
 enum KernelId : int {
     kKidNone = 0,

@@ -39,6 +39,17 @@ static int fail(int code, const char* fmt, ...) {
 
 extern "C" const char* rpo_last_error(void) { return g_err; }
 
+extern "C" int rpo_probe_peaks(const void* src_dev, void* dst_dev, size_t bytes, float* scratch_dev,
+                               double* copy_gbps, double* mfma_tflops, void* stream) {
+    if (!src_dev || !dst_dev || !scratch_dev || !copy_gbps || !mfma_tflops)
+        return fail(RPO_EINVAL, "rpo_probe_peaks: NULL argument");
+    if (bytes < ((size_t)1 << 20) || bytes % 16 != 0)
+        return fail(RPO_EINVAL, "rpo_probe_peaks: bytes must be a multiple of 16 and at least 1 MiB");
+    HIP_TRY(probe_copy(src_dev, dst_dev, bytes, 3, copy_gbps, (hipStream_t)stream));
+    HIP_TRY(probe_mfma(scratch_dev, 300000, 2, mfma_tflops, (hipStream_t)stream));
+    return RPO_OK;
+}
+
 extern "C" int rpo_set_kernel_path(int path) {
     if (path != 0 && path != 1 && path != 2 && !(path >= 17 && path <= 22) && path != 27)
         return fail(RPO_EINVAL, "kernel path must be 0, 1, 2, 17..22 or 27");
