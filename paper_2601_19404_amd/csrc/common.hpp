@@ -26,6 +26,13 @@ __host__ __device__ inline float bf16_to_f32(bf16 v) {
 }
 
 __host__ __device__ inline bf16 f32_to_bf16(float f) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    // the hardware conversion (round to nearest even, quiet NaN)
+    const __bf16 h = (__bf16)f;
+    bf16 r;
+    r.bits = __builtin_bit_cast(uint16_t, h);
+    return r;
+#else
     union {
         uint32_t u;
         float f;
@@ -40,6 +47,7 @@ __host__ __device__ inline bf16 f32_to_bf16(float f) {
     u += 0x7fffu + ((u >> 16) & 1u);  // round to nearest even
     r.bits = static_cast<uint16_t>(u >> 16);
     return r;
+#endif
 }
 
 template <typename T>

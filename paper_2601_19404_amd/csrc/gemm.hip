@@ -22,7 +22,8 @@ namespace rpo {
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 
-__device__ inline float silu_f(float g) { return g / (1.0f + __expf(-g)); }
+// g * sigmoid(g); the hardware reciprocal (1 ulp) replaces the IEEE division sequence
+__device__ inline float silu_f(float g) { return g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)); }
 
 // ---------------------------------------------------------------------------
 // generic kernel: 64x64 tile, 16-deep slabs, 256 threads, 4x4 outputs per thread
