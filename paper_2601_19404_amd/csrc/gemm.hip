@@ -382,7 +382,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const bf16* __res
                                                                void* __restrict__ Cv, int64_t ldc, int M,
                                                                int N, int K, int grid_m, int grid_n,
                                                                int n_tiles, int splits, int k_per_split, int F,
-                                                               RopeKvArgs rk) {
+                                                               RopeKvArgs rk, LseFuse lf) {
     constexpr int NW = WM * WN;
     constexpr int TM = BM / WM, TN = BN / WN;
     constexpr int MI = TM / 32, NI = TN / 32;
@@ -395,6 +395,10 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const bf16* __res
     static_assert(BM % (ROWS_PER_INST * NW) == 0 && BN % (ROWS_PER_INST * NW) == 0, "tile/wave mismatch");
     static_assert(!SWIGLU || NI % 2 == 0, "SwiGLU needs gate/up block pairs inside a wave");
     static_assert(STAGES >= 2 && STAGES <= 4, "pipeline depth");
+    // kEpiLse multiplies with the operands swapped: the accumulators then hold the transposed
+    // block, lane = row of A (l % 32), registers = 16 columns 8 * (e / 4) + 4 * (l / 32) + (e % 4),
+    // so that reductions along N stay inside a lane (plus one exchange between the lane halves).
+    constexpr bool kTrans = EPI == kEpiLse;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     bf16* As = (bf16*)smem_raw;             // [STAGES][BM][BK]
@@ -491,7 +495,8 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const bf16* __res
                 for (int i = 0; i < MI; ++i)
 #pragma unroll
                     for (int j = 0; j < NI; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][i], bfr[cur][j], acc[i][j], 0, 0, 0);
+                        acc[i][j] = kTrans ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cur][j], af[cur][i], acc[i][j], 0, 0, 0)
+                                           : __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][i], bfr[cur][j], acc[i][j], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
             asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kInFlight) : "memory");
@@ -500,7 +505,48 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const bf16* __res
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // drain the redundant tail loads before LDS is released
     }
 #undef RPO_DMA_SLAB
-    if constexpr (EPI == kEpiRope) {
+    if constexpr (EPI == kEpiLse) {
+        const int half = lane >> 5;
+        const int blk = (n0 / BN) * WN + wn;
+        const int cbase = n0 + wn * TN;
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+            const int r = m0 + wm * TM + i * 32 + (lane & 31);
+            const int tgt = r < M ? lf.target[r] : -1;
+            float mx = -INFINITY, zt = 0.f;
+            bool have = false;
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int col = cbase + j * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
+                    const float v = col < N ? acc[i][j][e] : -INFINITY;
+                    acc[i][j][e] = v;
+                    mx = fmaxf(mx, v);
+                    if (col == tgt) {
+                        zt = v;
+                        have = true;
+                    }
+                }
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float muse = mx == -INFINITY ? 0.f : mx;
+            const float nb = -muse * lf.k2;
+            float sum = 0.f;
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) sum += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[i][j][e], lf.k2, nb));
+            sum += __shfl_xor(sum, 32, 64);
+            if (r < M) {
+                if (half == 0) {
+                    float* p = lf.part + ((int64_t)r * lf.blocks + blk) * 2;
+                    p[0] = mx;
+                    p[1] = sum;
+                }
+                if (have) lf.target_logit[r] = zt;
+            }
+        }
+    } else if constexpr (EPI == kEpiRope) {
         // The tile is BM rows of one head (BN = head_dim = 128, checked by the launcher).  The
         // accumulators go to LDS as fp32 [BM][BN + 1]; the rotation pairs (i, i + 64) of a row
         // then sit in one place whatever wave produced them.  q is rotated and stored to C, k is
@@ -843,10 +889,11 @@ hipError_t launch_one(const GemmArgs& a, int splits, void* out, hipStream_t s) {
         }
         kern<<<grid, block, lds, s>>>((const bf16*)a.A, a.lda, (const bf16*)a.W, a.ldw, out, a.ldc, a.M, a.N, a.K,
                                       gm, gn, n_tiles, splits, k_per_split, a.N / 2,
-                                      (EPI == kEpiRope && a.rope) ? *a.rope : RopeKvArgs{});
+                                      (EPI == kEpiRope && a.rope) ? *a.rope : RopeKvArgs{},
+                                      (EPI == kEpiLse && a.lse) ? *a.lse : LseFuse{});
         return hipGetLastError();
     }
-    if constexpr (EPI == kEpiRope) {
+    if constexpr (EPI == kEpiRope || EPI == kEpiLse) {
         return hipErrorInvalidValue;  // only the direct-to-LDS kernel has this epilogue
     } else {
         const size_t lds = (size_t)2 * (BM + BN) * kLdsRow * sizeof(bf16);
@@ -951,6 +998,12 @@ hipError_t launch_generic(const GemmArgs& a, hipStream_t s) {
 
 }  // namespace
 
+int gemm_fuses_lse(const GemmArgs& a) {
+    if (a.epilogue != kEpiStoreF32 || !mfma_ok(a) || a.K % kBK != 0 || a.path == 2) return 0;
+    if (pick_tile(a).id != kKidGemm256) return 0;
+    return ceil_div(a.N, 256) * 4;  // one block per wave column of a 256-wide tile
+}
+
 int gemm_kernel_id(const GemmArgs& a) {
     if (!mfma_ok(a)) return kKidGemmGeneric;
     return pick_tile(a).id;
@@ -988,6 +1041,10 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
     } else {
         const TileCfg t = pick_tile(a);
         const int splits = (a.ws && a.ws_bytes) ? pick_splits(a, t) : 1;
+        if (a.lse && gemm_fuses_lse(a) > 0) {
+            a.lse->blocks = gemm_fuses_lse(a);
+            return launch_one<256, 256, 2, 4, kEpiLse, false>(a, 1, nullptr, s);
+        }
         e = launch_gemm_only(a, splits, t, s);
         norm_done = want_norm && splits > 1 && norm_fusable(a);  // fused into the K-split reduction
         rope_done = (splits > 1 && rope_fusable(a)) || (t.id == kKidGemm32 && rope_direct(a));

@@ -26,6 +26,17 @@ enum Epilogue : int {
     kEpiSwiglu = 3,    // W = [gate rows; up rows] (N = 2F): C[M, F] = silu(A Wg^T) * (A Wu^T), input dtype
     kEpiPartial = 4,   // internal: fp32 partial sums of one K split
     kEpiRope = 5,      // internal: rotary embedding + KV page write from the accumulators (QKV projection)
+    kEpiLse = 8,       // internal: no C; per row and 64-column block the maximum and the sum of
+                       // 2^((z - max) k2), plus the value at the row's target column (LM head of the
+                       // log-prob pass: the logits never reach memory)
+};
+// Outputs of the kEpiLse epilogue (GemmArgs::lse): see launch_lse_combine for what follows.
+struct LseFuse {
+    float* part = nullptr;          // [M, blocks, 2] (max, sum) per row and column block
+    float* target_logit = nullptr;  // [M] z[row, target[row]]
+    const int32_t* target = nullptr;  // [M] column ids (out of range: target_logit untouched)
+    float k2 = 0.f;                 // log2(e) / temperature
+    int blocks = 0;                 // filled in by the launch: column blocks per row
 };
 struct RopeKvArgs;
 struct GemmArgs {
@@ -51,8 +62,14 @@ struct GemmArgs {
     // row and write k, v into the KV pages (rope->qkv must be C).  Fused into the K-split
     // reduction when the problem is split (the rotation then reads the fp32 sums: one rounding).
     const RopeKvArgs* rope = nullptr;
+    // Optional, with kEpiStoreF32 only (the LM head of the log-prob pass): if the launch can fuse the
+    // log-sum-exp (gemm_fuses_lse), C is not written and *lse receives the partial results instead.
+    LseFuse* lse = nullptr;
 };
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
+// Whether launch_gemm would honour GemmArgs::lse for these arguments, and with how many column
+// blocks per row (0 = it would write C as usual).
+int gemm_fuses_lse(const GemmArgs& a);
 
 // Practical-ceiling probes (probes.hip): a plain copy (GB/s, read + write) and an MFMA issue loop.
 hipError_t probe_copy(const void* src, void* dst, size_t bytes, int reps, double* gbps, hipStream_t s);
@@ -176,6 +193,11 @@ struct SampleArgs {
 hipError_t launch_sample(const SampleArgs& a, hipStream_t s);
 
 // out[r] = logits[r, target[r]] * inv_t - logsumexp(logits[r, :] * inv_t)
+// out[r] = (target_logit[r] - M) / T - ln(sum_b part[r, b].sum * 2^((part[r, b].max - M) k2)),
+// M = max_b part[r, b].max: the log-softmax value of the target from the pieces kEpiLse leaves.
+// (NaN for a target outside [0, vocab))
+hipError_t launch_lse_combine(const float* part, int blocks, const float* target_logit, const int32_t* target,
+                              int vocab, float inv_t, float* out, int rows, hipStream_t s);
 hipError_t launch_lse_gather(const float* logits, int64_t row_stride, int vocab, const int32_t* target,
                              float inv_t, float* out, int rows, hipStream_t s);
 

@@ -518,6 +518,47 @@ hipError_t lm_head_rows(rpo_batch* b, const int32_t* row_idx, int n, float* logi
                 kEpiStoreF32, s);
 }
 
+// final RMSNorm of selected rows + LM head + log-softmax value of each row's target token.
+// On the MFMA path the log-sum-exp is taken in the GEMM epilogue (the logits never reach memory);
+// `scratch` (the logits staging area) then holds the per-block pieces.
+hipError_t lm_head_logprob_rows(rpo_batch* b, const int32_t* row_idx, int n, const int32_t* target, float inv_t,
+                                float* out, float* scratch, hipStream_t s) {
+    const rpo_model* m = b->m;
+    const rpo_model_desc& d = m->d;
+    void* hl = b->at<void>(b->L.hl);
+    RET_IF(launch_rmsnorm(b->at<float>(b->L.x), row_idx, m->final_norm, d.dtype, d.d_model, d.rms_eps, hl, n,
+                          s));
+    GemmArgs g;
+    g.A = hl;
+    g.lda = d.d_model;
+    g.W = m->lm_head;
+    g.ldw = d.d_model;
+    g.C = scratch;
+    g.ldc = d.vocab;
+    g.M = n;
+    g.N = d.vocab;
+    g.K = d.d_model;
+    g.dtype = d.dtype;
+    g.epilogue = kEpiStoreF32;
+    g.path = g_kernel_path;
+    const int blocks = gemm_fuses_lse(g);
+    if (blocks <= 0) {
+        RET_IF(gemm(b, hl, d.d_model, m->lm_head, d.d_model, scratch, d.vocab, n, d.vocab, d.d_model, kEpiStoreF32,
+                    s));
+        return launch_lse_gather(scratch, d.vocab, d.vocab, target, inv_t, out, n, s);
+    }
+    LseFuse lf;
+    lf.part = scratch;                                   // [n, blocks, 2]
+    lf.target_logit = scratch + (size_t)n * blocks * 2;  // [n]
+    lf.target = target;
+    lf.k2 = inv_t * 1.4426950408889634f;
+    g.lse = &lf;
+    const double es = (double)dtype_size(g.dtype);
+    RET_IF(timed(gemm_kernel_id(g), 2.0 * n * (double)d.vocab * d.d_model,
+                 ((double)n * d.d_model + (double)d.vocab * d.d_model) * es, s, [&] { return launch_gemm(g, s); }));
+    return launch_lse_combine(lf.part, lf.blocks, lf.target_logit, target, d.vocab, inv_t, out, n, s);
+}
+
 template <typename T>
 hipError_t upload(rpo_batch* b, std::vector<std::vector<T>>& keep, const std::vector<T>& v, size_t off,
                   hipStream_t s) {
@@ -758,10 +799,8 @@ extern "C" int rpo_suffix_logprobs(rpo_batch* b, const int32_t* suffix_tokens_de
         const int out0 = cu_suffix_host[r0];
         for (int c0 = 0; c0 < n_lm; c0 += lm_chunk) {
             const int n = std::min(lm_chunk, n_lm - c0);
-            float* logits = b->at<float>(L.logits);
-            HIP_TRY(lm_head_rows(b, b->at<int32_t>(L.lm_idx) + c0, n, logits, s));
-            HIP_TRY(launch_lse_gather(logits, d.vocab, d.vocab, suffix_tokens_dev + out0 + c0, inv_t,
-                                      logprobs_out_dev + out0 + c0, n, s));
+            HIP_TRY(lm_head_logprob_rows(b, b->at<int32_t>(L.lm_idx) + c0, n, suffix_tokens_dev + out0 + c0, inv_t,
+                                         logprobs_out_dev + out0 + c0, b->at<float>(L.logits), s));
         }
         if (r1 == r0) return fail(RPO_EINVAL, "rpo_suffix_logprobs: a suffix does not fit max_rows");
         r0 = r1;

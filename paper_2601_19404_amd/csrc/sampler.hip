@@ -259,6 +259,37 @@ __global__ __launch_bounds__(256) void lse_gather_kernel(const float* __restrict
     }
 }
 
+// One wave per row: merge the (max, sum) pieces of the fused LM-head epilogue.
+__global__ __launch_bounds__(64) void lse_combine_kernel(const float* __restrict__ part, int blocks,
+                                                         const float* __restrict__ target_logit,
+                                                         const int32_t* __restrict__ target, int vocab, float inv_t,
+                                                         float* __restrict__ out) {
+    const int r = blockIdx.x, lane = threadIdx.x;
+    const float* p = part + (int64_t)r * blocks * 2;
+    float mx = -INFINITY;
+    for (int b = lane; b < blocks; b += 64) mx = fmaxf(mx, p[2 * b]);
+    mx = wave_max(mx);
+    const float k2 = inv_t * 1.4426950408889634f;
+    float sum = 0.f;
+    for (int b = lane; b < blocks; b += 64) {
+        const float m = p[2 * b];
+        if (m != -INFINITY) sum += p[2 * b + 1] * exp2f((m - mx) * k2);
+    }
+    sum = wave_sum(sum);
+    if (lane == 0) {
+        const int t = target[r];
+        const float zt = (t >= 0 && t < vocab) ? target_logit[r] : NAN;  // as launch_lse_gather
+        out[r] = (zt - mx) * inv_t - logf(sum);
+    }
+}
+
+hipError_t launch_lse_combine(const float* part, int blocks, const float* target_logit, const int32_t* target,
+                              int vocab, float inv_t, float* out, int rows, hipStream_t s) {
+    if (rows <= 0) return hipSuccess;
+    lse_combine_kernel<<<rows, 64, 0, s>>>(part, blocks, target_logit, target, vocab, inv_t, out);
+    return hipGetLastError();
+}
+
 hipError_t launch_lse_gather(const float* logits, int64_t row_stride, int vocab, const int32_t* target,
                              float inv_t, float* out, int rows, hipStream_t s) {
     if (rows <= 0) return hipSuccess;
