@@ -206,6 +206,45 @@ def test_bf16_two_kv_heads_many_rollouts_mfma(rpo):
     run_case(rpo, BF16_2KV, p, a, m, G=16, max_rows=300, abs_tol=False)
 
 
+BF16_WIDE_VOCAB = synth.ModelCfg("bf16-wide-vocab", 2, 768, 6, 1, 128, 1024, 33000, "bf16")
+
+
+def test_bf16_wide_vocab_fused_logprobs(rpo):
+    """A vocabulary wide enough (129 column tiles, the last one ragged) and enough scored rows that
+    the log-prob pass takes its log-sum-exp inside the LM-head epilogue; checked against the oracle
+    like every other case, and against the unfused path (register-staged GEMM, logits in memory)."""
+    from paper_2601_19404_amd import rollout
+    p, a, m = bf16_workload(BF16_WIDE_VOCAB, lens=(70, 100, 130), ms=(12, 9, 11), seed=4)
+    _, res = run_case(rpo, BF16_WIDE_VOCAB, p, a, m, G=4)
+    order = rollout.order_by_suffix_length(m)
+    prompts = [p[i] for i in order]
+    cached = [a[i] for i in order]
+    ms = np.asarray(m)[order]
+    outs = []
+    for path in (0, 2):
+        rpo.rpo_set_kernel_path(path)
+        w = synth.perturb_gains(synth.make_weights(BF16_WIDE_VOCAB, seed=1234))
+        model = rpo.rpo_model_create(BF16_WIDE_VOCAB, util.to_device(w))
+        toks, cu = rollout.cut_and_pack(prompts, cached, ms)
+        batch = rpo.rpo_batch_create(model, 3, 4, int(max(np.diff(cu))), int(ms.max()), 64, 256)
+        last = torch.empty(3, BF16_WIDE_VOCAB.vocab, device="cuda")
+        rpo.rpo_prefill_prefix(batch, torch.from_numpy(toks).cuda(), cu, last)
+        rpo.rpo_kv_fork(batch)
+        packed, cu_s = rollout.pack_suffixes(res.tokens, ms, 4)
+        packed = packed.clone()
+        packed[5] = -3                                   # a target outside the vocabulary scores NaN
+        out = torch.zeros(int(cu_s[-1]), dtype=torch.float32, device="cuda")
+        rpo.rpo_suffix_logprobs(batch, packed, cu_s, 1.0, out)
+        torch.cuda.synchronize()
+        outs.append(out.cpu().numpy())
+    rpo.rpo_set_kernel_path(0)
+    assert np.isnan(outs[0][5]) and np.isnan(outs[1][5])
+    ok = np.ones(len(outs[0]), bool)
+    ok[5] = False
+    ok[6] = False    # the row after the bad token was fed an out-of-range embedding id
+    assert np.max(np.abs(outs[0][ok] - outs[1][ok])) < 2e-2
+
+
 def test_decode_active_mask_and_row_prefix(rpo):
     """Rows masked out by `active` must not disturb the live ones; a shorter leading block works."""
     from paper_2601_19404_amd import rollout
