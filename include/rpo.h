@@ -132,10 +132,13 @@ int rpo_kv_fork(rpo_batch *b, void *stream);
  *   active_dev device uint8 [n_rows] or NULL (all live).  A row with 0 appends
  *              no K/V; its logits row holds unspecified values.
  *   logits_dev device fp32 [n_rows, vocab]
+ *   row_max_out_dev device fp32 [n_rows] or NULL: max_i logits[r, i] of every row (the exact
+ *              fp32 maximum; taken in the LM-head epilogue where the kernel allows, so that
+ *              rpo_sample need not sweep the row for it).  Unspecified for rows with active 0.
  * The step counter is kept by the batch (all live rows advance together).
  * Errors: RPO_ESTATE before fork or beyond max_suffix; RPO_EINVAL. */
 int rpo_decode_step(rpo_batch *b, const int32_t *tokens_dev, int32_t n_rows,
-                    const uint8_t *active_dev, float *logits_dev, void *stream);
+                    const uint8_t *active_dev, float *logits_dev, float *row_max_out_dev, void *stream);
 
 /* Draw one token per output row from softmax(logits / temperature) (the paper
  * samples with a temperature, Sec. 4.1).  Stateless.  The draw is defined through
@@ -161,12 +164,15 @@ int rpo_decode_step(rpo_batch *b, const int32_t *tokens_dev, int32_t n_rows,
  *                     draws eos_id is set to 0 (pass the same array to rpo_decode_step).
  *   lengths_inout_dev device int32 [n_out_rows] or NULL: incremented for every live row (the
  *                     end-of-sequence token counts).
+ *   row_max_dev       device fp32 [n_logit_rows] or NULL.  If given, row_max_dev[k] MUST equal the
+ *                     maximum of logits row k exactly (rpo_decode_step's row_max_out_dev); the
+ *                     sampler then skips its own maximum sweep.  A wrong value gives a wrong draw.
  * NaN logits give undefined tokens.  Errors: RPO_EINVAL (sizes, temperature <= 0). */
 int rpo_sample(const float *logits_dev, int32_t n_logit_rows, int32_t vocab, int64_t row_stride,
                const int32_t *row_map_dev, int32_t n_out_rows, float temperature, uint64_t seed,
                const uint64_t *seq_id_dev, uint32_t step, int32_t *tokens_out_dev,
                float *logprob_out_dev, int32_t eos_id, uint8_t *active_inout_dev,
-               int32_t *lengths_inout_dev, void *stream);
+               int32_t *lengths_inout_dev, const float *row_max_dev, void *stream);
 
 /* log pi(o_j | q, o_<j) of every suffix token (the quantity the ratio of Eq. 7 is
  * made of), teacher-forced: for each rollout row r the suffix tokens are pushed

@@ -66,8 +66,8 @@ def lib() -> C.CDLL:
     L.rpo_batch_destroy.restype = None
     L.rpo_prefill_prefix.argtypes = [vp, vp, C.POINTER(i32), vp, vp]
     L.rpo_kv_fork.argtypes = [vp, vp]
-    L.rpo_decode_step.argtypes = [vp, vp, i32, vp, vp, vp]
-    L.rpo_sample.argtypes = [vp, i32, i32, i64, vp, i32, f32, u64, vp, u32, vp, vp, i32, vp, vp, vp]
+    L.rpo_decode_step.argtypes = [vp, vp, i32, vp, vp, vp, vp]
+    L.rpo_sample.argtypes = [vp, i32, i32, i64, vp, i32, f32, u64, vp, u32, vp, vp, i32, vp, vp, vp, vp]
     L.rpo_suffix_logprobs.argtypes = [vp, vp, C.POINTER(i32), f32, vp, vp]
     L.grpo_advantages.argtypes = [vp, i32, i32, i32, f32, vp, vp]
     L.rpo_objective_forward.argtypes = [vp, vp, vp, vp, vp, i32, i32, f32, f32, vp, vp, vp, vp]
@@ -222,19 +222,23 @@ def rpo_kv_fork(batch: Batch, stream=None) -> None:
 
 
 def rpo_decode_step(batch: Batch, tokens_dev: torch.Tensor, n_rows: int, active_dev, logits_dev: torch.Tensor,
-                    stream=None) -> None:
+                    stream=None, row_max_out_dev=None) -> None:
     if tokens_dev.numel() < n_rows or logits_dev.numel() < n_rows * batch.model.cfg.vocab:
         raise ValueError("tokens_dev / logits_dev smaller than n_rows")
+    if row_max_out_dev is not None and (row_max_out_dev.dtype != torch.float32 or row_max_out_dev.numel() < n_rows):
+        raise ValueError("row_max_out_dev must be float32 with at least n_rows elements")
     _check(lib().rpo_decode_step(batch.handle, tokens_dev.data_ptr(), n_rows, _ptr(active_dev),
-                                 logits_dev.data_ptr(), _stream(stream)))
+                                 logits_dev.data_ptr(), _ptr(row_max_out_dev), _stream(stream)))
 
 
 def rpo_sample(logits_dev: torch.Tensor, n_logit_rows: int, vocab: int, row_stride: int, row_map_dev,
                n_out_rows: int, temperature: float, seed: int, seq_id_dev: torch.Tensor, step: int,
                tokens_out_dev: torch.Tensor, logprob_out_dev=None, stream=None, eos_id: int = -1,
-               active_inout_dev=None, lengths_inout_dev=None) -> None:
+               active_inout_dev=None, lengths_inout_dev=None, row_max_dev=None) -> None:
     if logits_dev.dtype != torch.float32 or tokens_out_dev.dtype != torch.int32:
         raise ValueError("logits must be float32, tokens int32")
+    if row_max_dev is not None and (row_max_dev.dtype != torch.float32 or row_max_dev.numel() < n_logit_rows):
+        raise ValueError("row_max_dev must be float32 with at least n_logit_rows elements")
     if logits_dev.numel() < (n_logit_rows - 1) * row_stride + vocab:
         raise ValueError("logits_dev smaller than n_logit_rows x row_stride")
     if seq_id_dev.numel() < n_out_rows or tokens_out_dev.numel() < n_out_rows:
@@ -242,7 +246,7 @@ def rpo_sample(logits_dev: torch.Tensor, n_logit_rows: int, vocab: int, row_stri
     _check(lib().rpo_sample(logits_dev.data_ptr(), n_logit_rows, vocab, row_stride, _ptr(row_map_dev),
                             n_out_rows, temperature, seed, seq_id_dev.data_ptr(), step,
                             tokens_out_dev.data_ptr(), _ptr(logprob_out_dev), eos_id, _ptr(active_inout_dev),
-                            _ptr(lengths_inout_dev), _stream(stream)))
+                            _ptr(lengths_inout_dev), _ptr(row_max_dev), _stream(stream)))
 
 
 def rpo_suffix_logprobs(batch: Batch, suffix_tokens_dev: torch.Tensor, cu_suffix_host, temperature: float,

@@ -398,7 +398,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const bf16* __res
     // kEpiLse multiplies with the operands swapped: the accumulators then hold the transposed
     // block, lane = row of A (l % 32), registers = 16 columns 8 * (e / 4) + 4 * (l / 32) + (e % 4),
     // so that reductions along N stay inside a lane (plus one exchange between the lane halves).
-    constexpr bool kTrans = EPI == kEpiLse;
+    constexpr bool kTrans = EPI == kEpiLse || EPI == kEpiLogitsMax;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     bf16* As = (bf16*)smem_raw;             // [STAGES][BM][BK]
@@ -545,6 +545,31 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const bf16* __res
                 }
                 if (have) lf.target_logit[r] = zt;
             }
+        }
+    } else if constexpr (EPI == kEpiLogitsMax) {
+        // transposed accumulators: a lane owns a row and, per register quad, four consecutive columns
+        const int half = lane >> 5;
+        const int blk = (n0 / BN) * WN + wn;
+        const int cbase = n0 + wn * TN;
+        float* C = (float*)Cv;
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+            const int r = m0 + wm * TM + i * 32 + (lane & 31);
+            float mx = -INFINITY;
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int col = cbase + j * 32 + 8 * q + 4 * half;
+                    if (r < M && col < N) {  // N is a multiple of 4 (checked by the launcher): whole quads
+                        const float4 v = float4{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2],
+                                                acc[i][j][4 * q + 3]};
+                        *(float4*)(C + (int64_t)r * ldc + col) = v;
+                        mx = fmaxf(fmaxf(mx, fmaxf(v.x, v.y)), fmaxf(v.z, v.w));
+                    }
+                }
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            if (r < M && half == 0) lf.part[(int64_t)r * lf.blocks + blk] = mx;
         }
     } else if constexpr (EPI == kEpiRope) {
         // The tile is BM rows of one head (BN = head_dim = 128, checked by the launcher).  The
@@ -890,10 +915,11 @@ hipError_t launch_one(const GemmArgs& a, int splits, void* out, hipStream_t s) {
         kern<<<grid, block, lds, s>>>((const bf16*)a.A, a.lda, (const bf16*)a.W, a.ldw, out, a.ldc, a.M, a.N, a.K,
                                       gm, gn, n_tiles, splits, k_per_split, a.N / 2,
                                       (EPI == kEpiRope && a.rope) ? *a.rope : RopeKvArgs{},
-                                      (EPI == kEpiLse && a.lse) ? *a.lse : LseFuse{});
+                                      (EPI == kEpiLse && a.lse) ? *a.lse
+                                      : (EPI == kEpiLogitsMax && a.block_max) ? *a.block_max : LseFuse{});
         return hipGetLastError();
     }
-    if constexpr (EPI == kEpiRope || EPI == kEpiLse) {
+    if constexpr (EPI == kEpiRope || EPI == kEpiLse || EPI == kEpiLogitsMax) {
         return hipErrorInvalidValue;  // only the direct-to-LDS kernel has this epilogue
     } else {
         const size_t lds = (size_t)2 * (BM + BN) * kLdsRow * sizeof(bf16);
@@ -1004,6 +1030,13 @@ int gemm_fuses_lse(const GemmArgs& a) {
     return ceil_div(a.N, 256) * 4;  // one block per wave column of a 256-wide tile
 }
 
+int gemm_fuses_max(const GemmArgs& a) {
+    if (gemm_fuses_lse(a) == 0) return 0;  // same kernel shape
+    // the transposed epilogue stores 16-byte column quads
+    if (a.N % 4 != 0 || a.ldc % 4 != 0 || (uintptr_t)a.C % 16 != 0) return 0;
+    return ceil_div(a.N, 256) * 4;
+}
+
 int gemm_kernel_id(const GemmArgs& a) {
     if (!mfma_ok(a)) return kKidGemmGeneric;
     return pick_tile(a).id;
@@ -1044,6 +1077,10 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
         if (a.lse && gemm_fuses_lse(a) > 0) {
             a.lse->blocks = gemm_fuses_lse(a);
             return launch_one<256, 256, 2, 4, kEpiLse, false>(a, 1, nullptr, s);
+        }
+        if (a.block_max && gemm_fuses_max(a) > 0) {
+            a.block_max->blocks = gemm_fuses_max(a);
+            return launch_one<256, 256, 2, 4, kEpiLogitsMax, false>(a, 1, a.C, s);
         }
         e = launch_gemm_only(a, splits, t, s);
         norm_done = want_norm && splits > 1 && norm_fusable(a);  // fused into the K-split reduction

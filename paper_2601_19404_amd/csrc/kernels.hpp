@@ -29,6 +29,7 @@ enum Epilogue : int {
     kEpiLse = 8,       // internal: no C; per row and 64-column block the maximum and the sum of
                        // 2^((z - max) k2), plus the value at the row's target column (LM head of the
                        // log-prob pass: the logits never reach memory)
+    kEpiLogitsMax = 9, // internal: kEpiStoreF32 that also leaves each row's maximum per 64-column block
 };
 // Outputs of the kEpiLse epilogue (GemmArgs::lse): see launch_lse_combine for what follows.
 struct LseFuse {
@@ -65,11 +66,18 @@ struct GemmArgs {
     // Optional, with kEpiStoreF32 only (the LM head of the log-prob pass): if the launch can fuse the
     // log-sum-exp (gemm_fuses_lse), C is not written and *lse receives the partial results instead.
     LseFuse* lse = nullptr;
+    // Optional, with kEpiStoreF32 only (the LM head of a decode step): if the launch can (gemm_fuses_max),
+    // it also writes block_max->part[row, block] = max of the row over that column block.
+    LseFuse* block_max = nullptr;
 };
 hipError_t launch_gemm(const GemmArgs& a, hipStream_t s);
 // Whether launch_gemm would honour GemmArgs::lse for these arguments, and with how many column
 // blocks per row (0 = it would write C as usual).
 int gemm_fuses_lse(const GemmArgs& a);
+int gemm_fuses_max(const GemmArgs& a);
+// out[r] = max_b part[r, b]  /  out[r] = max_i logits[r, i]
+hipError_t launch_row_max_blocks(const float* part, int blocks, float* out, int rows, hipStream_t s);
+hipError_t launch_row_max(const float* logits, int64_t row_stride, int vocab, float* out, int rows, hipStream_t s);
 
 // Practical-ceiling probes (probes.hip): a plain copy (GB/s, read + write) and an MFMA issue loop.
 hipError_t probe_copy(const void* src, void* dst, size_t bytes, int reps, double* gbps, hipStream_t s);
@@ -189,6 +197,7 @@ struct SampleArgs {
     int eos_id;          // < 0: no end-of-sequence token
     uint8_t* active;     // in/out per output row, or NULL: all rows live
     int32_t* lengths;    // in/out per output row (tokens generated so far), or NULL
+    const float* row_max = nullptr;  // per logits row: its maximum, or NULL: the kernel finds it
 };
 hipError_t launch_sample(const SampleArgs& a, hipStream_t s);
 

@@ -175,7 +175,7 @@ bool make_dims(const rpo_model* m, int n_groups, int G, int max_prefix, int max_
 
 // Workspace carve-up (byte offsets, each 256-aligned).
 struct WsLayout {
-    size_t x, h, qkv, attn, gu, act, hl, logits, partial, rope, tables, group_desc, rollout_desc,
+    size_t x, h, qkv, attn, gu, act, hl, logits, blkmax, partial, rope, tables, group_desc, rollout_desc,
         chunk_desc, row_seq, tok_index, lm_idx, shared_pages, fork_src, fork_dst, last_idx, total;
 };
 
@@ -198,6 +198,7 @@ WsLayout make_layout(const rpo_model* m, const BatchDims& bd) {
     L.act = take(R * (size_t)d.d_ffn * es);
     L.hl = take((size_t)bd.lm_rows * d.d_model * es);
     L.logits = take((size_t)std::min(bd.max_rows, 1024) * d.vocab * 4);
+    L.blkmax = take((size_t)bd.B * ((size_t)ceil_div(d.vocab, 256) * 4) * 4);  // row maxima per column block
     L.partial = take(attn_decode_partial_floats(bd.B, d.n_q_heads, d.head_dim, bd.ppg) * 4);
     L.rope = take((size_t)bd.max_pos * d.head_dim * 4);
     L.tables = take(((size_t)bd.n_groups * bd.ppg + (size_t)bd.B * bd.table_len) * 4);
@@ -391,6 +392,27 @@ struct PassCfg {
         hipError_t e__ = (expr);           \
         if (e__ != hipSuccess) return e__; \
     } while (0)
+
+GemmArgs gemm_args(rpo_batch* b, const void* A, int64_t lda, const void* W, int64_t ldw, void* C, int64_t ldc,
+                   int M, int N, int K, int epi) {
+    GemmArgs g;
+    g.A = A;
+    g.lda = lda;
+    g.W = W;
+    g.ldw = ldw;
+    g.C = C;
+    g.ldc = ldc;
+    g.M = M;
+    g.N = N;
+    g.K = K;
+    g.dtype = b->m->d.dtype;
+    g.epilogue = epi;
+    g.path = g_kernel_path;
+    g.ws = b->at<void>(b->L.gu);
+    g.ws_bytes = kSplitKBytes;
+    g.norm_eps = b->m->d.rms_eps;
+    return g;
+}
 
 hipError_t gemm(rpo_batch* b, const void* A, int64_t lda, const void* W, int64_t ldw, void* C,
                 int64_t ldc, int M, int N, int K, int epi, hipStream_t s, const void* norm_gain = nullptr,
@@ -675,7 +697,8 @@ extern "C" int rpo_kv_fork(rpo_batch* b, void* stream) {
 
 // ---------------------------------------------------------------------------
 extern "C" int rpo_decode_step(rpo_batch* b, const int32_t* tokens_dev, int32_t n_rows,
-                               const uint8_t* active_dev, float* logits_dev, void* stream) {
+                               const uint8_t* active_dev, float* logits_dev, float* row_max_out_dev,
+                               void* stream) {
     if (!b || !tokens_dev || !logits_dev) return fail(RPO_EINVAL, "rpo_decode_step: NULL argument");
     if (b->state != kForked) return fail(RPO_ESTATE, "rpo_decode_step: call rpo_kv_fork first");
     const BatchDims& bd = b->bd;
@@ -717,8 +740,26 @@ extern "C" int rpo_decode_step(rpo_batch* b, const int32_t* tokens_dev, int32_t 
     }
     pc.final_norm_out = b->at<void>(L.hl);
     HIP_TRY(run_layers(b, pc, s));
-    HIP_TRY(gemm(b, b->at<void>(L.hl), d.d_model, b->m->lm_head, d.d_model, logits_dev, d.vocab, n_rows, d.vocab,
-                 d.d_model, kEpiStoreF32, s));
+    if (!row_max_out_dev) {
+        HIP_TRY(gemm(b, b->at<void>(L.hl), d.d_model, b->m->lm_head, d.d_model, logits_dev, d.vocab, n_rows, d.vocab,
+                     d.d_model, kEpiStoreF32, s));
+    } else {
+        // the LM-head epilogue leaves each row's maximum per column block where it can
+        GemmArgs g = gemm_args(b, b->at<void>(L.hl), d.d_model, b->m->lm_head, d.d_model, logits_dev, d.vocab, n_rows,
+                               d.vocab, d.d_model, kEpiStoreF32);
+        LseFuse bm;
+        bm.part = b->at<float>(L.blkmax);
+        g.block_max = &bm;
+        const bool fused = gemm_fuses_max(g) > 0;
+        const double es = (double)dtype_size(g.dtype);
+        HIP_TRY(timed(gemm_kernel_id(g), 2.0 * n_rows * (double)d.vocab * d.d_model,
+                      ((double)n_rows * d.d_model + (double)d.vocab * d.d_model) * es + (double)n_rows * d.vocab * 4.0,
+                      s, [&] { return launch_gemm(g, s); }));
+        if (fused)
+            HIP_TRY(launch_row_max_blocks(bm.part, bm.blocks, row_max_out_dev, n_rows, s));
+        else
+            HIP_TRY(launch_row_max(logits_dev, d.vocab, d.vocab, row_max_out_dev, n_rows, s));
+    }
     b->step += 1;
     return RPO_OK;
 }
@@ -813,7 +854,7 @@ extern "C" int rpo_sample(const float* logits_dev, int32_t n_logit_rows, int32_t
                           const int32_t* row_map_dev, int32_t n_out_rows, float temperature, uint64_t seed,
                           const uint64_t* seq_id_dev, uint32_t step, int32_t* tokens_out_dev,
                           float* logprob_out_dev, int32_t eos_id, uint8_t* active_inout_dev,
-                          int32_t* lengths_inout_dev, void* stream) {
+                          int32_t* lengths_inout_dev, const float* row_max_dev, void* stream) {
     if (!logits_dev || !seq_id_dev || !tokens_out_dev) return fail(RPO_EINVAL, "rpo_sample: NULL argument");
     if (n_logit_rows < 1 || vocab < 1 || vocab > 262144 || row_stride < vocab || n_out_rows < 0)
         return fail(RPO_EINVAL, "rpo_sample: bad sizes (vocab 1..262144, row_stride >= vocab)");
@@ -836,6 +877,7 @@ extern "C" int rpo_sample(const float* logits_dev, int32_t n_logit_rows, int32_t
     a.eos_id = eos_id >= vocab ? -1 : eos_id;
     a.active = active_inout_dev;
     a.lengths = lengths_inout_dev;
+    a.row_max = row_max_dev;
     HIP_TRY(timed(kKidSample, 0.0, (double)n_out_rows * vocab * 4.0, (hipStream_t)stream,
                   [&] { return launch_sample(a, (hipStream_t)stream); }));
     return RPO_OK;

@@ -119,14 +119,18 @@ __global__ __launch_bounds__(256) void sample_kernel(SampleArgs a) {
     const bool vec = ((uintptr_t)z % 16) == 0;
 
     float zmax = -INFINITY;
-    for (int i = tid * 4; i < V; i += 1024) {
-        const float4 v = load4(z, i, V, vec);
-        zmax = fmaxf(fmaxf(zmax, fmaxf(v.x, v.y)), fmaxf(v.z, v.w));
+    if (a.row_max) {  // the caller (the LM-head epilogue) already knows the row's maximum
+        zmax = a.row_max[src];
+    } else {
+        for (int i = tid * 4; i < V; i += 1024) {
+            const float4 v = load4(z, i, V, vec);
+            zmax = fmaxf(fmaxf(zmax, fmaxf(v.x, v.y)), fmaxf(v.z, v.w));
+        }
+        zmax = wave_max(zmax);
+        if (lane == 0) red[wave] = zmax;
+        __syncthreads();
+        zmax = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
     }
-    zmax = wave_max(zmax);
-    if (lane == 0) red[wave] = zmax;
-    __syncthreads();
-    zmax = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
 
     for (int sg = wave; sg < n_seg; sg += 4) {
         uint64_t q = 0;  // < 16 * 2^41
@@ -257,6 +261,41 @@ __global__ __launch_bounds__(256) void lse_gather_kernel(const float* __restrict
         const float zt = (t >= 0 && t < vocab) ? z[t] : NAN;
         out[r] = (zt - mx) * inv_t - logf(tot);
     }
+}
+
+// One wave per row: the maximum over its block maxima / over the row itself.
+__global__ __launch_bounds__(64) void row_max_blocks_kernel(const float* __restrict__ part, int blocks,
+                                                            float* __restrict__ out) {
+    const int r = blockIdx.x, lane = threadIdx.x;
+    float mx = -INFINITY;
+    for (int b = lane; b < blocks; b += 64) mx = fmaxf(mx, part[(int64_t)r * blocks + b]);
+    mx = wave_max(mx);
+    if (lane == 0) out[r] = mx;
+}
+
+__global__ __launch_bounds__(256) void row_max_kernel(const float* __restrict__ logits, int64_t row_stride, int vocab,
+                                                      float* __restrict__ out) {
+    __shared__ float red[4];
+    const int r = blockIdx.x, tid = threadIdx.x;
+    const float* z = logits + (int64_t)r * row_stride;
+    float mx = -INFINITY;
+    for (int i = tid; i < vocab; i += 256) mx = fmaxf(mx, z[i]);
+    mx = wave_max(mx);
+    if ((tid & 63) == 0) red[tid >> 6] = mx;
+    __syncthreads();
+    if (tid == 0) out[r] = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+}
+
+hipError_t launch_row_max_blocks(const float* part, int blocks, float* out, int rows, hipStream_t s) {
+    if (rows <= 0) return hipSuccess;
+    row_max_blocks_kernel<<<rows, 64, 0, s>>>(part, blocks, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_row_max(const float* logits, int64_t row_stride, int vocab, float* out, int rows, hipStream_t s) {
+    if (rows <= 0) return hipSuccess;
+    row_max_kernel<<<rows, 256, 0, s>>>(logits, row_stride, vocab, out);
+    return hipGetLastError();
 }
 
 // One wave per row: merge the (max, sum) pieces of the fused LM-head epilogue.

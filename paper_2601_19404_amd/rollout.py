@@ -69,6 +69,7 @@ def suffix_rollout(batch: rpo.Batch, prompts, cached, m, temperature: float, see
     out_tokens = torch.zeros((max_m, B), dtype=torch.int32, device="cuda")
     out_lp = torch.zeros((max_m, B), dtype=torch.float32, device="cuda")
     row_map = torch.arange(B, dtype=torch.int32, device="cuda") // G
+    row_max = torch.empty(B, dtype=torch.float32, device="cuda")   # per-row logits maximum from the LM head
     active = lengths = None
     eos = -1
     if eos_id is not None:
@@ -102,9 +103,9 @@ def suffix_rollout(batch: rpo.Batch, prompts, cached, m, temperature: float, see
         n = live_groups[j] * G
         if n == 0:
             break
-        rpo.rpo_decode_step(batch, out_tokens[j - 1], n, active, logits, stream)
+        rpo.rpo_decode_step(batch, out_tokens[j - 1], n, active, logits, stream, row_max)
         rpo.rpo_sample(logits, n, V, V, None, n, temperature, seed, seq_ids, j, out_tokens[j],
-                       out_lp[j], stream, eos, active, lengths)
+                       out_lp[j], stream, eos, active, lengths, row_max)
         if j < n_keep:
             kept.append(logits[:n].clone())
     mark("decode")

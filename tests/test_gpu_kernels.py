@@ -137,6 +137,12 @@ def test_sampler_bit_exact(rpo, vocab, rows, temperature):
         otok, olp = osampler.sample(z, temperature, 12345678901234, seq, step)
         np.testing.assert_array_equal(tok.cpu().numpy(), otok)
         np.testing.assert_allclose(lp.cpu().numpy(), olp, atol=1e-4)
+        # the same draw when the caller hands over the row maxima
+        tok2 = torch.empty(rows, dtype=torch.int32, device="cuda")
+        rpo.rpo_sample(zd, rows, vocab, vocab, None, rows, temperature, 12345678901234, seqd, step, tok2,
+                       row_max_dev=zd.max(dim=1).values.contiguous())
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(tok2.cpu().numpy(), otok)
     assert tok.cpu().numpy()[1] == vocab - 1 if rows > 1 else True
 
 

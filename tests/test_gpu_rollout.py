@@ -245,6 +245,32 @@ def test_bf16_wide_vocab_fused_logprobs(rpo):
     assert np.max(np.abs(outs[0][ok] - outs[1][ok])) < 2e-2
 
 
+@pytest.mark.parametrize("mcfg,rows_per_group", [(BF16_WIDE_VOCAB, 32), (BF16_SMALL, 4)])
+def test_decode_row_max_output(rpo, mcfg, rows_per_group):
+    """rpo_decode_step's row maxima equal the maxima of the logits it returns, bit for bit: from the
+    LM-head epilogue (wide vocabulary, 96 rows) and from the plain kernel (small problem)."""
+    from paper_2601_19404_amd import rollout
+    rpo.rpo_set_kernel_path(0)
+    model = rpo.rpo_model_create(mcfg, util.to_device(synth.make_weights(mcfg, seed=9)))
+    p, a, m = bf16_workload(mcfg, lens=(70, 100, 130), ms=(4, 4, 4), seed=6)
+    G, ng, V = rows_per_group, 3, mcfg.vocab
+    toks, cu = rollout.cut_and_pack(p, a, m)
+    batch = rpo.rpo_batch_create(model, ng, G, int(max(np.diff(cu))), 8, 64, 256)
+    last = torch.empty(ng, V, device="cuda")
+    rpo.rpo_prefill_prefix(batch, torch.from_numpy(toks).cuda(), cu, last)
+    rpo.rpo_kv_fork(batch)
+    B = ng * G
+    step_tok = (torch.arange(B, dtype=torch.int32, device="cuda") * 7 + 3) % V
+    for n in (B, B - G):
+        logits = torch.full((B, V), float("nan"), device="cuda")
+        ref = torch.empty_like(logits)
+        rmax = torch.full((B,), float("nan"), device="cuda")
+        rpo.rpo_decode_step(batch, step_tok, n, None, logits, row_max_out_dev=rmax)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(rmax[:n].cpu().numpy(), logits[:n].max(dim=1).values.cpu().numpy())
+        assert np.all(np.isfinite(logits[:n].cpu().numpy()))
+
+
 def test_decode_active_mask_and_row_prefix(rpo):
     """Rows masked out by `active` must not disturb the live ones; a shorter leading block works."""
     from paper_2601_19404_amd import rollout
