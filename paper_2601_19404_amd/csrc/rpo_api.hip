@@ -750,6 +750,12 @@ extern "C" int rpo_decode_step(rpo_batch* b, const int32_t* tokens_dev, int32_t 
         LseFuse bm;
         bm.part = b->at<float>(L.blkmax);
         g.block_max = &bm;
+        // A handful of rows streams the LM-head weights either way: keep the 256-wide tile whose
+        // epilogue knows the maxima rather than sweep the logits again.
+        if (g.path == 0 && gemm_fuses_max(g) == 0) {
+            g.path = 16 + kKidGemm256;
+            if (gemm_fuses_max(g) == 0) g.path = 0;
+        }
         const bool fused = gemm_fuses_max(g) > 0;
         const double es = (double)dtype_size(g.dtype);
         HIP_TRY(timed(gemm_kernel_id(g), 2.0 * n_rows * (double)d.vocab * d.d_model,

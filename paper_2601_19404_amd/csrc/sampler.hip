@@ -132,19 +132,30 @@ __global__ __launch_bounds__(256) void sample_kernel(SampleArgs a) {
         zmax = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
     }
 
+    // The logits of the wave's next segment are loaded while the weights of the current one are
+    // computed (-inf beyond the row: weight 0).
+    float4 cur[4], nxt[4];
+#pragma unroll
+    for (int sb = 0; sb < 4; ++sb) cur[sb] = load4(z, wave * kSegLen + sb * kSubLen + lane * 4, V, vec);
     for (int sg = wave; sg < n_seg; sg += 4) {
+        const bool more = sg + 4 < n_seg;  // wave-uniform
+        if (more) {
+#pragma unroll
+            for (int sb = 0; sb < 4; ++sb) nxt[sb] = load4(z, (sg + 4) * kSegLen + sb * kSubLen + lane * 4, V, vec);
+        }
         uint64_t q = 0;  // < 16 * 2^41
 #pragma unroll
         for (int sb = 0; sb < 4; ++sb) {
-            const int i0 = sg * kSegLen + sb * kSubLen + lane * 4;
-            if (i0 < V) {
-                const float4 v = load4(z, i0, V, vec);
-                q += weight_u64(v.x, zmax, a.inv_t) + weight_u64(v.y, zmax, a.inv_t) +
-                     weight_u64(v.z, zmax, a.inv_t) + weight_u64(v.w, zmax, a.inv_t);
-            }
+            const float4 v = cur[sb];
+            q += weight_u64(v.x, zmax, a.inv_t) + weight_u64(v.y, zmax, a.inv_t) +
+                 weight_u64(v.z, zmax, a.inv_t) + weight_u64(v.w, zmax, a.inv_t);
         }
         q = wave_sum_u45(q);
         if (lane == 0) seg_sum[sg] = q;
+        if (more) {
+#pragma unroll
+            for (int sb = 0; sb < 4; ++sb) cur[sb] = nxt[sb];
+        }
     }
     __syncthreads();
 
@@ -263,14 +274,17 @@ __global__ __launch_bounds__(256) void lse_gather_kernel(const float* __restrict
     }
 }
 
-// One wave per row: the maximum over its block maxima / over the row itself.
-__global__ __launch_bounds__(64) void row_max_blocks_kernel(const float* __restrict__ part, int blocks,
-                                                            float* __restrict__ out) {
-    const int r = blockIdx.x, lane = threadIdx.x;
+// One workgroup per row: the maximum over its block maxima / over the row itself.
+__global__ __launch_bounds__(256) void row_max_blocks_kernel(const float* __restrict__ part, int blocks,
+                                                             float* __restrict__ out) {
+    __shared__ float red[4];
+    const int r = blockIdx.x, tid = threadIdx.x;
     float mx = -INFINITY;
-    for (int b = lane; b < blocks; b += 64) mx = fmaxf(mx, part[(int64_t)r * blocks + b]);
+    for (int b = tid; b < blocks; b += 256) mx = fmaxf(mx, part[(int64_t)r * blocks + b]);
     mx = wave_max(mx);
-    if (lane == 0) out[r] = mx;
+    if ((tid & 63) == 0) red[tid >> 6] = mx;
+    __syncthreads();
+    if (tid == 0) out[r] = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
 }
 
 __global__ __launch_bounds__(256) void row_max_kernel(const float* __restrict__ logits, int64_t row_stride, int vocab,
@@ -278,8 +292,12 @@ __global__ __launch_bounds__(256) void row_max_kernel(const float* __restrict__ 
     __shared__ float red[4];
     const int r = blockIdx.x, tid = threadIdx.x;
     const float* z = logits + (int64_t)r * row_stride;
+    const bool vec = ((uintptr_t)z % 16) == 0;
     float mx = -INFINITY;
-    for (int i = tid; i < vocab; i += 256) mx = fmaxf(mx, z[i]);
+    for (int i = tid * 4; i < vocab; i += 1024) {
+        const float4 v = load4(z, i, vocab, vec);  // -inf beyond the row
+        mx = fmaxf(fmaxf(mx, fmaxf(v.x, v.y)), fmaxf(v.z, v.w));
+    }
     mx = wave_max(mx);
     if ((tid & 63) == 0) red[tid >> 6] = mx;
     __syncthreads();
@@ -288,7 +306,7 @@ __global__ __launch_bounds__(256) void row_max_kernel(const float* __restrict__ 
 
 hipError_t launch_row_max_blocks(const float* part, int blocks, float* out, int rows, hipStream_t s) {
     if (rows <= 0) return hipSuccess;
-    row_max_blocks_kernel<<<rows, 64, 0, s>>>(part, blocks, out);
+    row_max_blocks_kernel<<<rows, 256, 0, s>>>(part, blocks, out);
     return hipGetLastError();
 }
 
