@@ -71,6 +71,11 @@ int rpo_set_kernel_path(int path);
  * Host-side only (event create / record / synchronise); not thread-safe.
  * Errors: RPO_EINVAL (unknown id, NULL), RPO_EHIP. */
 int rpo_profile_start(int kernel_id);
+/* The same, but only every `every`-th launch of the kernel (the 1st, the every+1-th, ...) is
+ * bracketed and counted: event pairs around each of thousands of short launches would slow the
+ * run that is being measured.  rpo_profile_stop then reports the bracketed launches only (their
+ * number, time, flops and bytes).  Errors: RPO_EINVAL (unknown id, every < 1). */
+int rpo_profile_start_sampled(int kernel_id, int every);
 int rpo_profile_stop(int64_t *n_launches, double *total_ms, double *total_flops, double *total_bytes);
 
 #ifdef __cplusplus

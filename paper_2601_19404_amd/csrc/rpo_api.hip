@@ -66,6 +66,8 @@ struct Profile {
     std::vector<hipEvent_t> events;  // pool, reused across sessions
     size_t used = 0;
     double flops = 0.0, bytes = 0.0;
+    int every = 1;      // time every n-th launch of the kernel only
+    int64_t seen = 0;   // launches of the kernel since rpo_profile_start
     hipError_t mark(hipStream_t s) {
         if (used == events.size()) {
             hipEvent_t e;
@@ -81,7 +83,7 @@ Profile g_prof;
 // Runs `launch` and, when kernel `id` is the one being timed, brackets it with events.
 template <typename F>
 hipError_t timed(int id, double flops, double bytes, hipStream_t s, F&& launch) {
-    const bool on = id != 0 && id == g_prof.kernel_id;
+    const bool on = id != 0 && id == g_prof.kernel_id && (g_prof.seen++ % g_prof.every) == 0;
     if (on) {
         hipError_t e = g_prof.mark(s);
         if (e != hipSuccess) return e;
@@ -97,13 +99,18 @@ hipError_t timed(int id, double flops, double bytes, hipStream_t s, F&& launch) 
 }
 }  // namespace
 
-extern "C" int rpo_profile_start(int kernel_id) {
+extern "C" int rpo_profile_start_sampled(int kernel_id, int every) {
     if (kernel_id <= 0 || kernel_id >= kKidCount) return fail(RPO_EINVAL, "rpo_profile_start: unknown kernel id");
+    if (every < 1) return fail(RPO_EINVAL, "rpo_profile_start_sampled: every must be >= 1");
     g_prof.kernel_id = kernel_id;
     g_prof.used = 0;
     g_prof.flops = g_prof.bytes = 0.0;
+    g_prof.every = every;
+    g_prof.seen = 0;
     return RPO_OK;
 }
+
+extern "C" int rpo_profile_start(int kernel_id) { return rpo_profile_start_sampled(kernel_id, 1); }
 
 extern "C" int rpo_profile_stop(int64_t* n_launches, double* total_ms, double* total_flops, double* total_bytes) {
     if (!n_launches || !total_ms || !total_flops || !total_bytes)
