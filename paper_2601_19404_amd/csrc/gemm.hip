@@ -152,6 +152,110 @@ __device__ inline void gemm_epilogue(f32x16_t (&acc)[MI][NI], void* __restrict__
     }
 }
 
+// Epilogue for accumulators computed with the MFMA operands swapped (the direct-to-LDS kernel): lane l
+// holds ROW (l % 32) of each 32x32 block and, per register quad q, the four consecutive columns
+// 8 q + 4 (l / 32) .. + 3 -- so the result leaves in 16-byte (fp32) or 8-byte (bf16) pieces.
+template <int MI, int NI, int TM, int TN, int EPI>
+__device__ inline void gemm_epilogue_t(f32x16_t (&acc)[MI][NI], void* __restrict__ Cv, int64_t ldc, int M, int N,
+                                       int m0, int n0, int wm, int wn, int lane, int split) {
+    typedef unsigned short u16x4_t __attribute__((ext_vector_type(4)));
+    const int r_in = lane & 31, c_in = (lane >> 5) * 4;
+    if (EPI == kEpiSwiglu) {
+        // blocks (j, j + 1) = (gate, up) of output columns (n0 + wn*TN + j*32)/2 + column in block
+        bf16* C = (bf16*)Cv;
+        const bool vec = (ldc & 3) == 0 && ((uintptr_t)Cv & 7) == 0;
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+            const int gm = m0 + wm * TM + i * 32 + r_in;
+            if (gm >= M) continue;
+#pragma unroll
+            for (int j = 0; j < NI; j += 2) {
+                const int vn = n0 + wn * TN + j * 32;  // virtual column of the gate block
+                if (vn >= N) continue;                  // N = 2F is a multiple of 64: pairs are whole
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int oc = (vn >> 1) + 8 * q + c_in;
+                    u16x4_t o;
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+                        o[t] = f32_to_bf16(silu_f(acc[i][j][4 * q + t]) * acc[i][j + 1][4 * q + t]).bits;
+                    bf16* dst = C + (int64_t)gm * ldc + oc;
+                    if (vec) {
+                        *(u16x4_t*)dst = o;
+                    } else {
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) dst[t].bits = o[t];
+                    }
+                }
+            }
+        }
+        return;
+    }
+    if (EPI == kEpiStore) {
+        bf16* C = (bf16*)Cv;
+        const bool vec = (ldc & 3) == 0 && ((uintptr_t)Cv & 7) == 0;
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+            const int gm = m0 + wm * TM + i * 32 + r_in;
+            if (gm >= M) continue;
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int gn = n0 + wn * TN + j * 32 + 8 * q + c_in;
+                    bf16* dst = C + (int64_t)gm * ldc + gn;
+                    if (vec && gn + 3 < N) {
+                        u16x4_t o;
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) o[t] = f32_to_bf16(acc[i][j][4 * q + t]).bits;
+                        *(u16x4_t*)dst = o;
+                    } else {
+#pragma unroll
+                        for (int t = 0; t < 4; ++t)
+                            if (gn + t < N) dst[t] = f32_to_bf16(acc[i][j][4 * q + t]);
+                    }
+                }
+        }
+        return;
+    }
+    // fp32 results: store, accumulate, or K-split partial sums
+    const int64_t ld = EPI == kEpiPartial ? (int64_t)N : ldc;
+    float* C = (float*)Cv + (EPI == kEpiPartial ? (int64_t)split * M * (int64_t)N : 0);
+    const bool vec = (ld & 3) == 0 && ((uintptr_t)C & 15) == 0;
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+        const int gm = m0 + wm * TM + i * 32 + r_in;
+        if (gm >= M) continue;
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int gn = n0 + wn * TN + j * 32 + 8 * q + c_in;
+                float* dst = C + (int64_t)gm * ld + gn;
+                if (vec && gn + 3 < N) {
+                    float4 v = float4{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+                    if (EPI == kEpiAddF32) {
+                        const float4 c = *(const float4*)dst;
+                        v.x += c.x;
+                        v.y += c.y;
+                        v.z += c.z;
+                        v.w += c.w;
+                    }
+                    *(float4*)dst = v;
+                } else {
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+                        if (gn + t < N) {
+                            if (EPI == kEpiAddF32)
+                                dst[t] += acc[i][j][4 * q + t];
+                            else
+                                dst[t] = acc[i][j][4 * q + t];
+                        }
+                }
+            }
+    }
+}
+
 // ---------------------------------------------------------------------------
 // MFMA kernel.
 //
@@ -395,10 +499,12 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const bf16* __res
     static_assert(BM % (ROWS_PER_INST * NW) == 0 && BN % (ROWS_PER_INST * NW) == 0, "tile/wave mismatch");
     static_assert(!SWIGLU || NI % 2 == 0, "SwiGLU needs gate/up block pairs inside a wave");
     static_assert(STAGES >= 2 && STAGES <= 4, "pipeline depth");
-    // kEpiLse multiplies with the operands swapped: the accumulators then hold the transposed
-    // block, lane = row of A (l % 32), registers = 16 columns 8 * (e / 4) + 4 * (l / 32) + (e % 4),
-    // so that reductions along N stay inside a lane (plus one exchange between the lane halves).
-    constexpr bool kTrans = EPI == kEpiLse || EPI == kEpiLogitsMax;
+    // Every epilogue but the rotary one and the plain bf16 store (measured: 2-byte stores of 32
+    // neighbouring lanes beat 8-byte stores of 32 rows) multiplies with the operands swapped: the accumulators then
+    // hold the transposed block, lane = row of A (l % 32), registers = 16 columns
+    // 8 * (e / 4) + 4 * (l / 32) + (e % 4).  Results leave in 16-byte pieces, and reductions along N
+    // stay inside a lane (plus one exchange between the lane halves).
+    constexpr bool kTrans = EPI != kEpiRope && EPI != kEpiStore;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     bf16* As = (bf16*)smem_raw;             // [STAGES][BM][BK]
@@ -643,7 +749,10 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const bf16* __res
             }
         }
     } else {
-        gemm_epilogue<MI, NI, TM, TN, EPI>(acc, Cv, ldc, M, N, m0, n0, wm, wn, lane, tc.split);
+        if constexpr (kTrans)
+            gemm_epilogue_t<MI, NI, TM, TN, EPI>(acc, Cv, ldc, M, N, m0, n0, wm, wn, lane, tc.split);
+        else
+            gemm_epilogue<MI, NI, TM, TN, EPI>(acc, Cv, ldc, M, N, m0, n0, wm, wn, lane, tc.split);
     }
 }
 
