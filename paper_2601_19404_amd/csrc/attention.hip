@@ -469,7 +469,7 @@ hipError_t launch_attn_chunk(const AttnArgs& a, hipStream_t s) {
 static int decode_splits(int n_groups_live, int Hkv, int n_ct, int max_shared_pages) {
     if (max_shared_pages <= 0) return 1;
     int want = ceil_div(512, n_groups_live * Hkv * n_ct);
-    want = want < 1 ? 1 : (want > 16 ? 16 : want);
+    want = want < 1 ? 1 : (want > 8 ? 8 : want);
     const int cap = max_shared_pages / 2 > 0 ? max_shared_pages / 2 : 1;  // at least two pages per piece
     return want < cap ? want : cap;
 }
