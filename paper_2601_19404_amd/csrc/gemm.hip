@@ -1169,6 +1169,9 @@ static hipError_t launch_gemm_only(const GemmArgs& a, int splits, const TileCfg&
             return launch_tile<256, 192, 4, 2>(a, splits, s);
         default:
             if (deep_pipeline(a, t)) return launch_tile<64, 128, 1, 2, 4>(a, splits, s);
+            // up to two workgroups per CU: three stages (72 KiB each) still fit twice
+            if (a.K % kBK == 0 && a.path != 2 && ceil_div(a.M, 64) * ceil_div(a.N, 128) * splits <= 512)
+                return launch_tile<64, 128, 1, 2, 3>(a, splits, s);
             return launch_tile<64, 128, 1, 2>(a, splits, s);
     }
 }
