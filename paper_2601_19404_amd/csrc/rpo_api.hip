@@ -957,6 +957,12 @@ extern "C" int rpo_gemm_nt(const void* a_dev, int64_t lda, const void* w_dev, in
     g.path = g_kernel_path;
     g.ws = ws_dev;
     g.ws_bytes = ws_bytes;
-    HIP_TRY(launch_gemm(g, (hipStream_t)stream));
+    const double es = (double)dtype_size(dtype);
+    const double out_bytes = epilogue == kEpiStore ? (double)M * N * es
+                             : epilogue == kEpiStoreF32 ? (double)M * N * 4.0
+                             : epilogue == kEpiAddF32 ? (double)M * N * 8.0
+                                                      : (double)M * (N / 2) * es;
+    HIP_TRY(timed(gemm_kernel_id(g), 2.0 * M * N * K, ((double)M * K + (double)N * K) * es + out_bytes,
+                  (hipStream_t)stream, [&] { return launch_gemm(g, (hipStream_t)stream); }));
     return RPO_OK;
 }

@@ -254,3 +254,25 @@ def test_objective_forward(rpo):
     with pytest.raises(rpo.RpoError):
         rpo.rpo_objective_forward(dev(lp_new), dev(lp_old), None, dev(cu), dev(adv), ng, g, 0.2, 0.1,
                                   None, torch.empty(ng, device="cuda"))
+
+
+# ---------------------------------------------------------------------------
+def test_profile_sampling_and_peak_probe(rpo):
+    """Kernel timing brackets every n-th launch only; the peak probes return plausible rates."""
+    a = torch.randn(300, 1536, device="cuda").to(torch.bfloat16)
+    w = torch.randn(520, 1536, device="cuda").to(torch.bfloat16)
+    c = torch.zeros(300, 520, device="cuda")
+    rpo.rpo_set_kernel_path(17)                       # every launch below is kernel id 1
+    for every, expect in ((1, 10), (4, 3)):
+        rpo.rpo_profile_start(rpo.KERNEL_IDS["gemm256"], every)
+        for _ in range(10):
+            rpo.rpo_gemm_nt(a, w, c, 1, None)
+        n, ms, flops, nbytes = rpo.rpo_profile_stop()
+        assert n == expect and ms > 0.0
+        assert flops == pytest.approx(expect * 2.0 * 300 * 520 * 1536)
+    rpo.rpo_set_kernel_path(0)
+    with pytest.raises(rpo.RpoError):
+        rpo.rpo_profile_start(rpo.KERNEL_IDS["gemm256"], 0)
+    copy_gbps, mfma_tflops = rpo.rpo_probe_peaks(1 << 28)
+    assert 500.0 < copy_gbps < 8000.0                 # below the published HBM peak
+    assert 200.0 < mfma_tflops < 2500.0               # below the published bf16 MFMA peak
