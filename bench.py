@@ -21,13 +21,14 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-PEAK = {"hbm": (8000.0, "GB/s"), "mfma": (2500.0, "TFLOP/s")}
+PEAK = {"hbm": (8000.0, "GB/s"), "mfma": (2500.0, "TFLOP/s"), "alu": (157.3, "TFLOP/s")}
 # HBM-side bytes per launch of the dominant kernel's heaviest launch (prefill gate/up projection,
 # M=16384, N=17920, K=1536, SwiGLU epilogue), from two rocprofv3 --pmc runs (FETCH_SIZE x 2.0 and
 # WRITE_SIZE x 1.0 after calibration against a 1 GiB copy).
 GEMM256_TRAFFIC = dict(launch="prefill gate/up projection M=16384 N=17920 K=1536", read_bytes=1340.4e6,
                        write_bytes=293.6e6, algorithmic_bytes=105.4e6 + 293.6e6)
-KERNEL_BOUND = {"gemm256": "mfma", "gemm256x128": "mfma", "gemm128": "mfma", "gemm64": "mfma",
+KERNEL_BOUND = {"gemm256": "mfma", "gemm256x128": "mfma", "gemm256x192": "mfma", "gemm128": "mfma", "gemm64": "mfma",
+                "gemm32": "mfma", "gemm64x64": "mfma", "gemm_generic": "alu", "attn_chunk": "mfma",
                 "attn_decode": "hbm", "sample": "hbm"}
 
 
@@ -297,7 +298,7 @@ def main():
     bound = KERNEL_BOUND.get(args.profile_kernel, "hbm")
     peak, unit = PEAK[bound]
     if launches and k_ms > 0:
-        work = k_flops / 1e12 if bound == "mfma" else k_bytes / 1e9
+        work = k_bytes / 1e9 if bound == "hbm" else k_flops / 1e12
         achieved = work / (k_ms / 1e3)
     else:
         achieved = 0.0
@@ -333,7 +334,7 @@ def main():
         out["practical_peaks"] = dict(copy_GBps=round(copy_gbps, 1), mfma_bf16_TFLOPs=round(mfma_tflops, 1),
                                       note="plain copy (read + write) and bf16 32x32x16 MFMA issue loop, "
                                            "measured by rpo_probe_peaks in this run")
-        practical = mfma_tflops if bound == "mfma" else copy_gbps
+        practical = mfma_tflops if bound == "mfma" else copy_gbps if bound == "hbm" else 0.0
         roofline["frac_of_practical"] = achieved / practical if practical > 0 else None
     except rpo.RpoError as e:  # the probe is informational
         out["practical_peaks"] = dict(error=str(e))

@@ -6,7 +6,6 @@
 #include "common.hpp"
 
 namespace rpo {
-namespace {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
@@ -52,8 +51,6 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(float* __restrict__ out
         for (int e = 0; e < 16; ++e) s += acc[i][e];
     out[blockIdx.x * 256 + threadIdx.x] = s;
 }
-
-}  // namespace
 
 // reps timed launches after one warm-up; returns the best launch's rate
 hipError_t probe_copy(const void* src, void* dst, size_t bytes, int reps, double* gbps, hipStream_t s) {

@@ -453,6 +453,15 @@ hipError_t gemm(rpo_batch* b, const void* A, int64_t lda, const void* W, int64_t
                  [&] { return launch_gemm(g, s); });
 }
 
+// Algorithmic flops of one layer's causal attention over packed chunks: every row multiplies its
+// query heads with the keys and with the values of the positions it sees (2 * 2 * dh per pair).
+double chunk_attn_flops(const std::vector<SeqDesc>& descs, const rpo_model_desc& d) {
+    double pairs = 0.0;
+    for (const SeqDesc& sd : descs)
+        pairs += (double)sd.n_rows * sd.pos0 + 0.5 * (double)sd.n_rows * ((double)sd.n_rows + 1.0);
+    return 4.0 * pairs * d.n_q_heads * d.head_dim;
+}
+
 hipError_t run_layers(rpo_batch* b, const PassCfg& pc, hipStream_t s) {
     const rpo_model* m = b->m;
     const rpo_model_desc& d = m->d;
@@ -650,6 +659,7 @@ extern "C" int rpo_prefill_prefix(rpo_batch* b, const int32_t* tokens_dev, const
         pc.active = nullptr;
         pc.decode = false;
         pc.max_shared_pages = 0;
+        pc.attn_flops = chunk_attn_flops(descs, d);
         HIP_TRY(run_layers(b, pc, s));
         // keep each group's last residual row (rows [max_rows + g0, max_rows + g1) of x)
         HIP_TRY(launch_gather_rows(b->at<float>(L.x), b->at<int32_t>(L.last_idx), d.d_model,
@@ -845,6 +855,7 @@ extern "C" int rpo_suffix_logprobs(rpo_batch* b, const int32_t* suffix_tokens_de
             pc.active = nullptr;
             pc.decode = false;
             pc.max_shared_pages = 0;
+            pc.attn_flops = chunk_attn_flops(descs, d);
             HIP_TRY(run_layers(b, pc, s));
         }
         // LM head + log-softmax gather over the scoring rows of this chunk, lm_chunk rows at a time
