@@ -59,13 +59,14 @@ int rpo_set_kernel_path(int path);
  * of those launches as the library counts them (GEMM: 2MNK flops, operands + result bytes;
  * decode attention: K/V bytes with a group's shared prefix counted once per group; sampler:
  * the logits rows read once).  Kernel ids:
- *   1  gemm_mfma_kernel<256,256,2,4,..> (prefill-sized problems and wide decode projections)
- *   2  gemm_mfma_kernel<256,128,2,2,..> (only via rpo_set_kernel_path)
- *   3  gemm_mfma_kernel<128,128,2,2,..> (decode-sized problems, deep K)   4  gemm_mfma_kernel<64,128,1,2,..> (M <= 64)
- *   5  gemm_dma_kernel<32,128,1,4,..> (decode QKV projection: rotary embedding and KV page write in the epilogue)
- *   6  gemm_dma_kernel<64,64,2,2,..> (decode-sized problems, shallow K, no K split)
+ * (MFMA GEMM tile shapes <BM, BN, waves along M, waves along N>)
+ *   1  <256,256,2,4> (prefill-sized problems and wide decode projections)
+ *   2  <256,128,2,2> (only via rpo_set_kernel_path)
+ *   3  <128,128,2,2> (decode-sized problems, deep K)   4  <64,128,1,2> (the same for M <= 64)
+ *   5  <32,128,1,4> (decode QKV projection: rotary embedding and KV page write in the epilogue)
+ *   6  <64,64,2,2> (decode-sized problems, shallow K, no K split)
  *      (all epilogues of a tile shape together; a K-split launch includes its reduction)
- *   11 gemm_dma_kernel<256,192,4,2,..> (large M with a narrow N: fewer idle CUs in the last round of workgroups)
+ *   11 <256,192,4,2> (large M with a narrow N: fewer idle CUs in the last round of workgroups)
  *   7  gemm_generic_kernel      8  attn_decode_mfma_kernel (+ merge)   9  attn_chunk_mfma_kernel
  *   10 sample_kernel
  * Host-side only (event create / record / synchronise); not thread-safe.

@@ -1,20 +1,24 @@
 // C[M,N] (op)= A[M,K] * W[N,K]^T with fp32 accumulation: the dense contractions of
 // the decoder (QKV, O, gate/up, down, LM head).  Both operands are K-contiguous.
 //
-//  * gemm_mfma_kernel: bf16 operands on the CDNA4 matrix cores
-//    (v_mfma_f32_32x32x16_bf16).  64-deep K slabs are staged through LDS, double
-//    buffered; the next slab's global loads are in flight while the current slab is
-//    multiplied.  Tile shapes: 256x256 (prefill / log-prob passes), 256x128 and
-//    128x128 (decode batches), 64x128 (a handful of rows).  Skinny problems that would
-//    leave most of the 256 CUs idle are split along K; the fp32 partial sums go to a
-//    workspace and gemm_splitk_reduce_kernel applies the epilogue (deterministic: no
-//    floating-point atomics).  Workgroup ids are remapped so that the tiles sharing a
-//    weight tile run on the same XCD (each XCD has its own L2).
-//  * SwiGLU is fused into the gate/up projection: the kernel reads the weight rows in
-//    the order [32 gate | 32 up | 32 gate | ...], so each wave holds matching gate and
-//    up columns in neighbouring accumulator blocks and writes silu(gate) * up directly.
+//  * gemm_dma_kernel: bf16 operands on the CDNA4 matrix cores (v_mfma_f32_32x32x16_bf16).
+//    64-deep K slabs go from global memory straight into LDS (global_load_lds_dwordx4), two to
+//    four stages deep; fragments are double-buffered in registers.  Tile shapes and what they
+//    are for (pick_tile): 256x256 (many-tile problems: prefill / log-prob chunks, wide decode
+//    projections), 256x192 (large M with a narrow N), 128x128 and 64x128 (deep-K decode
+//    projections, split along K: the fp32 partial sums go to a workspace and a reduction kernel
+//    applies the epilogue -- deterministic, no floating-point atomics), 64x64 and 32x128
+//    (shallow-K decode projections, one tile per CU, no K split).  (tile, K-split) work items
+//    are dealt evenly to the 8 XCDs, neighbouring tiles to the same XCD (each has its own L2).
+//  * Epilogues ride on the accumulators: residual add, SwiGLU (the kernel reads the weight rows
+//    in the order [32 gate | 32 up | 32 gate | ...], so a wave holds matching gate and up
+//    columns), rotary embedding + KV page write (QKV projection of a decode step), log-sum-exp
+//    and row maxima (LM head).  All but the rotary one and the plain bf16 store multiply with
+//    the MFMA operands swapped, which leaves a lane with one row and runs of four columns.
+//  * gemm_mfma_kernel: the same tiling with register-staged LDS fills, for K that is not a
+//    multiple of 64 (and selectable for comparison).
 //  * gemm_generic_kernel: any dtype on the vector ALUs (fp32 tiny model, shapes the
-//    MFMA kernel does not take).
+//    MFMA kernels do not take).
 #include "kernels.hpp"
 
 namespace rpo {
@@ -270,8 +274,8 @@ __device__ inline void gemm_epilogue_t(f32x16_t (&acc)[MI][NI], void* __restrict
 constexpr int kBK = 64;
 constexpr int kLdsRow = kBK + 8;
 constexpr int kXcd = 8;  // XCDs of an MI355X; workgroup i is dispatched to XCD i % 8
-// Direct-to-LDS pipeline shape.  Measured on the prefill gate/up projection: 64-deep slabs in two
-// stages 907 TFLOP/s, 32-deep slabs in four stages 870, four waves of 128x128 833: not latency-bound.
+// Default direct-to-LDS pipeline shape.  Measured on the prefill gate/up projection: 64-deep slabs
+// in two stages beat 32-deep slabs in four stages and four waves of 128x128: not latency-bound.
 #ifndef RPO_DMA_BK
 #define RPO_DMA_BK 64
 #define RPO_DMA_STAGES 2

@@ -86,14 +86,15 @@ hipError_t probe_mfma(float* scratch, int iters, int reps, double* tflops, hipSt
 // Identifiers of the kernels whose launches can be timed (rpo_profile_start).
 enum KernelId : int {
     kKidNone = 0,
-    kKidGemm256 = 1,        // gemm_mfma_kernel<256,256,2,4,*> (large problems)
-    kKidGemm256x128 = 2,    // gemm_mfma_kernel<256,128,2,2,*> (tuning aid only)
-    kKidGemm128 = 3,        // gemm_mfma_kernel<128,128,2,2,*> (decode-sized problems, K split)
-    kKidGemm64 = 4,         // gemm_mfma_kernel<64,128,1,2,*>  (M <= 64)
-    kKidGemm32 = 5,         // gemm_dma_kernel<32,128,1,4,*>  (narrow decode projections, no K split)
-    kKidGemm64x64 = 6,      // gemm_dma_kernel<64,64,2,2,*>
+    // tile shapes of gemm_dma_kernel / gemm_mfma_kernel <BM, BN, waves along M, waves along N>
+    kKidGemm256 = 1,        // <256,256,2,4> (many-tile problems)
+    kKidGemm256x128 = 2,    // <256,128,2,2> (tuning aid only)
+    kKidGemm128 = 3,        // <128,128,2,2> (decode-sized problems with a deep K, K split)
+    kKidGemm64 = 4,         // <64,128,1,2>  (the same for M <= 64)
+    kKidGemm32 = 5,         // <32,128,1,4>  (decode QKV projection: one head per tile, no K split)
+    kKidGemm64x64 = 6,      // <64,64,2,2>   (decode-sized problems with a shallow K, no K split)
     kKidGemmGeneric = 7,
-    kKidGemm256x192 = 11,   // gemm_dma_kernel<256,192,4,2,*> (large M, narrow N: fewer idle CUs in the last round)
+    kKidGemm256x192 = 11,   // <256,192,4,2> (large M, narrow N: fewer idle CUs in the last round)
     kKidAttnDecode = 8,     // attn_decode_mfma_kernel
     kKidAttnChunk = 9,      // attn_chunk_mfma_kernel
     kKidSample = 10,        // sample_kernel
