@@ -412,30 +412,43 @@ __global__ __launch_bounds__(256) void attn_decode_mfma_kernel(AttnArgs a, Decod
     }
 }
 
-// One wave per (rollout row, query head): combine the pieces.
-__global__ __launch_bounds__(64) void attn_merge_kernel(const float* __restrict__ part_o,
-                                                        const float* __restrict__ part_ml, int n_pieces,
-                                                        int Hq, const uint8_t* __restrict__ active,
-                                                        bf16* __restrict__ out) {
-    const int row = blockIdx.x, head = blockIdx.y, lane = threadIdx.x;
+// One workgroup per rollout row, one thread per (query head, pair of output channels): combine
+// the pieces.  All loads of a thread are issued before any is used (at most kMaxPieces pieces).
+constexpr int kMaxPieces = 9;  // decode_splits() caps the prefix pieces at 8, plus the private one
+__global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict__ part_o,
+                                                         const float* __restrict__ part_ml, int n_pieces,
+                                                         int Hq, const uint8_t* __restrict__ active,
+                                                         bf16* __restrict__ out) {
+    const int row = blockIdx.x;
     if (active && !active[row]) return;
-    const int64_t base = ((int64_t)row * Hq + head) * n_pieces;
-    float mx = -INFINITY;
-    for (int p = 0; p < n_pieces; ++p) mx = fmaxf(mx, part_ml[2 * (base + p)]);
-    float lsum = 0.f, o0 = 0.f, o1 = 0.f;
-    for (int p = 0; p < n_pieces; ++p) {
-        const float m = part_ml[2 * (base + p)];
-        if (m == -INFINITY) continue;
-        const float w = exp2f(m - mx);
-        lsum += w * part_ml[2 * (base + p) + 1];
-        const float* po = part_o + (base + p) * kDh;
-        o0 += w * po[lane];
-        o1 += w * po[lane + 64];
+    for (int w = threadIdx.x; w < Hq * (kDh / 2); w += 256) {
+        const int head = w / (kDh / 2), c = (w % (kDh / 2)) * 2;
+        const int64_t base = ((int64_t)row * Hq + head) * n_pieces;
+        float m[kMaxPieces], l[kMaxPieces];
+        float2 o[kMaxPieces];
+#pragma unroll
+        for (int p = 0; p < kMaxPieces; ++p) {
+            const bool on = p < n_pieces;
+            m[p] = on ? part_ml[2 * (base + p)] : -INFINITY;
+            l[p] = on ? part_ml[2 * (base + p) + 1] : 0.f;
+            o[p] = on ? *(const float2*)(part_o + (base + p) * kDh + c) : float2{0.f, 0.f};
+        }
+        float mx = -INFINITY;
+#pragma unroll
+        for (int p = 0; p < kMaxPieces; ++p) mx = fmaxf(mx, m[p]);
+        float lsum = 0.f, o0 = 0.f, o1 = 0.f;
+#pragma unroll
+        for (int p = 0; p < kMaxPieces; ++p) {
+            const float wgt = m[p] == -INFINITY ? 0.f : exp2f(m[p] - mx);  // an empty piece has no weight
+            lsum += wgt * l[p];
+            o0 += wgt * o[p].x;
+            o1 += wgt * o[p].y;
+        }
+        const float inv = 1.0f / lsum;
+        bf16* dst = out + ((int64_t)row * Hq + head) * kDh + c;
+        dst[0] = f32_to_bf16(o0 * inv);
+        dst[1] = f32_to_bf16(o1 * inv);
     }
-    const float inv = 1.0f / lsum;
-    bf16* o = out + ((int64_t)row * Hq + head) * kDh;
-    o[lane] = f32_to_bf16(o0 * inv);
-    o[lane + 64] = f32_to_bf16(o1 * inv);
 }
 
 static bool mfma_attn_ok(const AttnArgs& a) {
@@ -502,8 +515,8 @@ hipError_t launch_attn_decode(const DecodeAttnArgs& d, hipStream_t s) {
     attn_decode_mfma_kernel<<<grid, 256, kAttnLds, s>>>(a, dg, d.shared_pages, part_o, part_ml);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    attn_merge_kernel<<<dim3(a.rows, a.Hq), 64, 0, s>>>(part_o, part_ml, dg.n_split + 1, a.Hq, a.active,
-                                                        (bf16*)a.out);
+    if (dg.n_split + 1 > kMaxPieces) return hipErrorInvalidValue;
+    attn_merge_kernel<<<a.rows, 256, 0, s>>>(part_o, part_ml, dg.n_split + 1, a.Hq, a.active, (bf16*)a.out);
     return hipGetLastError();
 }
 
