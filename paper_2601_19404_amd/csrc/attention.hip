@@ -74,7 +74,7 @@ __global__ __launch_bounds__(64) void attn_generic_kernel(AttnArgs a) {
                 const int pg = __shfl(page, t, 64);
                 if (d < dh) {
                     const int slot = (c0 + t) % pt;
-                    acc = fmaf(ps[t], to_f32<T>(pool[a.geom.v_block(a.layer, pg, kh) + (int64_t)d * pt + slot]),
+                    acc = fmaf(ps[t], to_f32<T>(pool[a.geom.v_block(a.layer, pg, kh) + a.geom.v_elem(slot, d)]),
                                acc);
                 }
             }
@@ -178,7 +178,8 @@ __device__ inline void attn_stream_pages(const bf16* const (&qptr)[NC], const in
         for (int i = 0; i < 4; ++i) {
             const int c = tid + i * 256;
             *(u32x4_t*)(Ks + buf * kKTile + (c >> 4) * kKRow + (c & 15) * 8) = rk[i];
-            *(u32x4_t*)(Vs + buf * kVTile + (c >> 3) * kVRow + (c & 7) * 8) = rv[i];
+            // V block piece c = (token group c / 128, channel c % 128) -> LDS row = channel
+            *(u32x4_t*)(Vs + buf * kVTile + (c & (kDh - 1)) * kVRow + (c >> 7) * 8) = rv[i];
         }
     };
 

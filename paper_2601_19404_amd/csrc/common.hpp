@@ -92,8 +92,9 @@ inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b; }
 //
 // pool[layer][page][K|V][kv_head][...]: for K the inner block is
 // [page_tokens][head_dim] (a token's key is contiguous), for V it is
-// [head_dim][page_tokens] (transposed: the tokens of one channel are contiguous,
-// which is the operand order the P*V matrix product wants).
+// [page_tokens / 8][head_dim][8] (transposed in groups of eight tokens: the P*V matrix product
+// wants eight consecutive tokens of one channel per lane, exactly one 16-byte unit, and a
+// token's head_dim values land 16 bytes apart -- 16 cache lines per token instead of 128).
 // ---------------------------------------------------------------------------
 struct KvGeom {
     int n_kv_heads, head_dim, page_tokens;
@@ -106,6 +107,10 @@ struct KvGeom {
     }
     __host__ __device__ int64_t v_block(int layer, int64_t page, int h) const {
         return layer * layer_stride() + page * page_stride() + (int64_t)(n_kv_heads + h) * head_block();
+    }
+    // element (token slot, channel d) inside a V block; page_tokens is a multiple of 8
+    __host__ __device__ int64_t v_elem(int slot, int d) const {
+        return ((int64_t)(slot >> 3) * head_dim + d) * 8 + (slot & 7);
     }
 };
 

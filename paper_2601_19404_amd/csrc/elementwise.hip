@@ -147,7 +147,7 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(RopeKvArgs a) {
     const int n_v = a.Hkv * dh;
     for (int w = threadIdx.x; w < n_v; w += 256) {
         const int kh = w / dh, d = w % dh;
-        pool[a.geom.v_block(a.layer, page, kh) + (int64_t)d * pt + slot] = vsrc[w];
+        pool[a.geom.v_block(a.layer, page, kh) + a.geom.v_elem(slot, d)] = vsrc[w];
     }
 }
 

@@ -740,16 +740,15 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const bf16* __res
                 dst[i + 64] = f32_to_bf16(y2);
             }
         } else {
-            // lanes run over rows: consecutive rows of one sequence fill consecutive slots
-            const int row = tid & 31;
-            const int pos = row_pos[row];
-            if (pos >= 0) {
-                bf16* vdst = pool + rk.geom.v_block(rk.layer, row_page[row], head - rk.Hq - rk.Hkv) + pos % pt;
+            // a wave writes 64 consecutive channels of one row: 2-byte pieces 16 bytes apart (8 lines)
+            const int d = tid & (BN - 1);
 #pragma unroll
-                for (int it = 0; it < BN / 8; ++it) {
-                    const int d = it * 8 + (tid >> 5);
-                    vdst[(int64_t)d * pt] = f32_to_bf16(tile[row * LD + d]);
-                }
+            for (int it = 0; it < BM / 2; ++it) {
+                const int row = it * 2 + (tid >> 7);
+                const int pos = row_pos[row];
+                if (pos < 0) continue;
+                pool[rk.geom.v_block(rk.layer, row_page[row], head - rk.Hq - rk.Hkv) + rk.geom.v_elem(pos % pt, d)] =
+                    f32_to_bf16(tile[row * LD + d]);
             }
         }
     } else {
@@ -898,7 +897,7 @@ __global__ __launch_bounds__(256) void gemm_splitk_reduce_rope_kernel(const floa
     const int v0 = (a.Hq + a.Hkv) * dh;
     for (int w = tid; w < a.Hkv * dh; w += 256) {
         const int kh = w / dh, d = w % dh;
-        pool[a.geom.v_block(a.layer, page, kh) + (int64_t)d * pt + slot] = f32_to_bf16(rowsum[v0 + w]);
+        pool[a.geom.v_block(a.layer, page, kh) + a.geom.v_elem(slot, d)] = f32_to_bf16(rowsum[v0 + w]);
     }
 }
 
