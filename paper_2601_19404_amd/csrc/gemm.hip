@@ -159,11 +159,42 @@ __device__ inline void gemm_epilogue(f32x16_t (&acc)[MI][NI], void* __restrict__
 // Epilogue for accumulators computed with the MFMA operands swapped (the direct-to-LDS kernel): lane l
 // holds ROW (l % 32) of each 32x32 block and, per register quad q, the four consecutive columns
 // 8 q + 4 (l / 32) .. + 3 -- so the result leaves in 16-byte (fp32) or 8-byte (bf16) pieces.
-template <int MI, int NI, int TM, int TN, int EPI>
+template <int MI, int NI, int TM, int TN, int EPI, int SW>
 __device__ inline void gemm_epilogue_t(f32x16_t (&acc)[MI][NI], void* __restrict__ Cv, int64_t ldc, int M, int N,
                                        int m0, int n0, int wm, int wn, int lane, int split) {
     typedef unsigned short u16x4_t __attribute__((ext_vector_type(4)));
     const int r_in = lane & 31, c_in = (lane >> 5) * 4;
+    if (EPI == kEpiSwiglu && SW == 2) {
+        // gate and up of output column (block's virtual column)/2 + 8 q + column-in-quad sit in
+        // registers 4 q + t and 4 (q + 2) + t of the same block (q = 0, 1)
+        bf16* C = (bf16*)Cv;
+        const bool vec = (ldc & 3) == 0 && ((uintptr_t)Cv & 7) == 0;
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+            const int gm = m0 + wm * TM + i * 32 + r_in;
+            if (gm >= M) continue;
+#pragma unroll
+            for (int j = 0; j < NI; ++j) {
+                const int vn = n0 + wn * TN + j * 32;
+                if (vn >= N) continue;  // N = 2F is a multiple of 32: blocks are whole
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    u16x4_t o;
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+                        o[t] = f32_to_bf16(silu_f(acc[i][j][4 * q + t]) * acc[i][j][4 * (q + 2) + t]).bits;
+                    bf16* dst = C + (int64_t)gm * ldc + (vn >> 1) + 8 * q + c_in;
+                    if (vec) {
+                        *(u16x4_t*)dst = o;
+                    } else {
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) dst[t].bits = o[t];
+                    }
+                }
+            }
+        }
+        return;
+    }
     if (EPI == kEpiSwiglu) {
         // blocks (j, j + 1) = (gate, up) of output columns (n0 + wn*TN + j*32)/2 + column in block
         bf16* C = (bf16*)Cv;
@@ -283,9 +314,14 @@ constexpr int kXcd = 8;  // XCDs of an MI355X; workgroup i is dispatched to XCD 
 
 // Column n of the (virtual) output -> row of W.  SwiGLU mode interleaves gate and up rows
 // in blocks of 32: virtual columns [64q, 64q+32) are gate rows 32q.., [64q+32, 64q+64) up rows.
-template <bool SWIGLU>
+// Mode 2 interleaves in blocks of 16 instead (virtual columns [32q, 32q+16) are gate rows 16q..,
+// [32q+16, 32q+32) up rows): with the transposed accumulators a lane then holds the gate and the
+// up value of an output in one 32x32 block (registers 4 q + t and 4 (q + 2) + t), whatever the
+// number of blocks per wave.
+template <int SWIGLU>
 __device__ inline int weight_row(int n, int F) {
-    if (!SWIGLU) return n;
+    if (SWIGLU == 0) return n;
+    if (SWIGLU == 2) return ((n >> 4) & 1) * F + ((n >> 5) << 4) + (n & 15);
     return ((n >> 5) & 1) * F + ((n >> 6) << 5) + (n & 31);
 }
 
@@ -321,7 +357,7 @@ __device__ inline TileCoord tile_coord(int n_tiles, int splits, int grid_m, int 
 
 // EPI: kEpiStore / kEpiStoreF32 / kEpiAddF32 / kEpiSwiglu write the result; kEpiPartial writes
 // fp32 partial sums of its K split to Cv[split][M][N].
-template <int BM, int BN, int WM, int WN, int EPI, bool SWIGLU>
+template <int BM, int BN, int WM, int WN, int EPI, int SWIGLU>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_kernel(const bf16* __restrict__ A, int64_t lda,
                                                                 const bf16* __restrict__ W, int64_t ldw,
                                                                 void* __restrict__ Cv, int64_t ldc,
@@ -333,7 +369,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_mfma_kernel(const bf16* __re
     constexpr int A_CHUNKS = BM * (kBK / 8) / NT;  // 16-byte pieces per thread and slab
     constexpr int B_CHUNKS = BN * (kBK / 8) / NT;
     static_assert(BM * (kBK / 8) % NT == 0 && BN * (kBK / 8) % NT == 0, "tile/thread mismatch");
-    static_assert(!SWIGLU || NI % 2 == 0, "SwiGLU needs gate/up block pairs inside a wave");
+    static_assert(SWIGLU != 1 || NI % 2 == 0, "SwiGLU needs gate/up block pairs inside a wave");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     bf16* As = (bf16*)smem_raw;                 // [2][BM][kLdsRow]
@@ -484,7 +520,7 @@ __device__ inline int lds_swizzle(int row) {
     return ((row >> 2) & 3) ^ (((row >> 1) & 1) << 1);
 }
 
-template <int BM, int BN, int WM, int WN, int EPI, bool SWIGLU, int BK, int STAGES>
+template <int BM, int BN, int WM, int WN, int EPI, int SWIGLU, int BK, int STAGES>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const bf16* __restrict__ A, int64_t lda,
                                                                const bf16* __restrict__ W, int64_t ldw,
                                                                void* __restrict__ Cv, int64_t ldc, int M,
@@ -501,7 +537,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const bf16* __res
     constexpr int A_STAGE = BM * BK, B_STAGE = BN * BK;  // elements
     static_assert(BK == 64 || BK == 32, "slab depth");
     static_assert(BM % (ROWS_PER_INST * NW) == 0 && BN % (ROWS_PER_INST * NW) == 0, "tile/wave mismatch");
-    static_assert(!SWIGLU || NI % 2 == 0, "SwiGLU needs gate/up block pairs inside a wave");
+    static_assert(SWIGLU != 1 || NI % 2 == 0, "SwiGLU needs gate/up block pairs inside a wave");
     static_assert(STAGES >= 2 && STAGES <= 4, "pipeline depth");
     // Every epilogue but the rotary one and the plain bf16 store (measured: 2-byte stores of 32
     // neighbouring lanes beat 8-byte stores of 32 rows) multiplies with the operands swapped: the accumulators then
@@ -753,7 +789,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const bf16* __res
         }
     } else {
         if constexpr (kTrans)
-            gemm_epilogue_t<MI, NI, TM, TN, EPI>(acc, Cv, ldc, M, N, m0, n0, wm, wn, lane, tc.split);
+            gemm_epilogue_t<MI, NI, TM, TN, EPI, SWIGLU>(acc, Cv, ldc, M, N, m0, n0, wm, wn, lane, tc.split);
         else
             gemm_epilogue<MI, NI, TM, TN, EPI>(acc, Cv, ldc, M, N, m0, n0, wm, wn, lane, tc.split);
     }
@@ -934,8 +970,9 @@ TileCfg pick_tile(const GemmArgs& a) {
             case kKidGemm128: return TileCfg{kKidGemm128, 128, 128};
             case kKidGemm32: return TileCfg{kKidGemm32, 32, 128};
             case kKidGemm64x64: return TileCfg{kKidGemm64x64, 64, 64};
-            case kKidGemm256x192:  // no fused gate/up epilogue for this shape
-                if (a.epilogue != kEpiSwiglu) return TileCfg{kKidGemm256x192, 256, 192};
+            case kKidGemm256x192:  // its fused gate/up epilogue exists on the direct-to-LDS kernel only
+                if (a.epilogue != kEpiSwiglu || (a.K % kBK == 0 && (a.N / 2) % 16 == 0))
+                    return TileCfg{kKidGemm256x192, 256, 192};
                 return TileCfg{kKidGemm256, 256, 256};
             default: return TileCfg{kKidGemm64, 64, 128};
         }
@@ -946,6 +983,11 @@ TileCfg pick_tile(const GemmArgs& a) {
     // four-deep load pipeline beat wider tiles whose K-split partial sums need a second kernel;
     // with a deep K, 128x128 tiles split along K.
     const int t256 = ceil_div(a.M, 256) * ceil_div(a.N, 256);
+    // The gate/up projection of a decode step: one round of fewer 256x256 tiles than CUs; 256x192
+    // tiles still fit one round and each is a quarter cheaper.
+    if (a.epilogue == kEpiSwiglu && a.M > 256 && t256 >= 128 && t256 <= 256 && a.K % kBK == 0 && a.path != 2 &&
+        (a.N / 2) % 16 == 0 && ceil_div(a.M, 256) * ceil_div(a.N, 192) <= 256)
+        return TileCfg{kKidGemm256x192, 256, 192};
     if (a.M > 512 || (a.M > 64 && t256 >= 128)) {
         // Workgroups run in rounds of one per CU.  A 256x192 tile costs about 0.78 of a 256x256
         // one; it wins when the wider tile would leave much of its last round idle (narrow N).
@@ -976,6 +1018,7 @@ bool deep_pipeline(const GemmArgs& a, const TileCfg& t) {
 // too few, and only when the workspace can hold the partials.
 int pick_splits(const GemmArgs& a, const TileCfg& t) {
     if (t.id == kKidGemm32 || t.id == kKidGemm64x64) return 1;
+    if (t.id == kKidGemm256x192 && a.epilogue == kEpiSwiglu) return 1;
     const int tiles = ceil_div(a.M, t.bm) * ceil_div(a.N, t.bn);
     if (tiles >= 128 || a.K < 1024) return 1;  // half a chip of tiles: splitting costs more than it gains
     // one workgroup per CU with the deep pipeline, two otherwise
@@ -999,7 +1042,7 @@ bool norm_fusable(const GemmArgs& a) {
            ((uintptr_t)a.norm_out % 8 == 0) && ((uintptr_t)a.norm_gain % 8 == 0);
 }
 
-template <int BM, int BN, int WM, int WN, int EPI, bool SWIGLU, int DST = RPO_DMA_STAGES, int DBK = RPO_DMA_BK>
+template <int BM, int BN, int WM, int WN, int EPI, int SWIGLU, int DST = RPO_DMA_STAGES, int DBK = RPO_DMA_BK>
 hipError_t launch_one(const GemmArgs& a, int splits, void* out, hipStream_t s) {
     // direct-to-LDS pipeline shape: DBK-deep slabs in DST stages
     const int gm = ceil_div(a.M, BM), gn = ceil_div(a.N, BN);
@@ -1169,6 +1212,7 @@ static hipError_t launch_gemm_only(const GemmArgs& a, int splits, const TileCfg&
         case kKidGemm64x64:
             return launch_tile<64, 64, 2, 2, 4>(a, splits, s);
         case kKidGemm256x192:
+            if (a.epilogue == kEpiSwiglu) return launch_one<256, 192, 4, 2, kEpiSwiglu, 2>(a, 1, a.C, s);
             return launch_tile<256, 192, 4, 2>(a, splits, s);
         default:
             if (deep_pipeline(a, t)) return launch_tile<64, 128, 1, 2, 4>(a, splits, s);
