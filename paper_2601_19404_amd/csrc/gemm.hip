@@ -326,12 +326,13 @@ __device__ inline int weight_row(int n, int F) {
 }
 
 // Tile order shared by the MFMA kernels.  A launch has n_tiles * splits work items (item =
-// split * n_tiles + logical tile).  Workgroup ids are dealt round-robin to the 8 XCDs, so the ids one
-// XCD sees (i % 8 == x) are mapped to one contiguous run of items, the runs as equal as possible:
-// a launch of about one workgroup per CU then really puts one on every CU.  Logical tiles are
-// grouped in blocks of blk_m x blk_n = 32 tiles (one per CU of an XCD): the workgroups running
-// together on an XCD share blk_m row slabs and blk_n weight slabs through its L2.  With at most 8
-// row tiles the order is plain column-major (blocks of grid_m x 1): no padding tiles.
+// split * n_tiles + logical tile, n_tiles = grid_m * grid_n: no padding items).  Workgroup ids are
+// dealt round-robin to the 8 XCDs, so the ids one XCD sees (i % 8 == x) are mapped to one
+// contiguous run of items, the runs as equal as possible: a launch of about one workgroup per
+// CU then really puts one on every CU.  Logical tiles walk the grid in column bands of 4 tile
+// columns (the last band narrower), each band in blocks of 8 tile rows (the last shorter),
+// each block column-major: the ~32 workgroups running together on an XCD share about 8 row slabs
+// and 4 weight slabs through its L2.
 struct TileCoord {
     int bm, bn, split;
     bool ok;
@@ -344,14 +345,26 @@ __device__ inline TileCoord tile_coord(int n_tiles, int splits, int grid_m, int 
     const int item = start + blockIdx.x / kXcd;
     if (item >= next) return t;
     t.split = item / n_tiles;
-    const int logical = item % n_tiles;
-    const int blk_m = grid_m < 8 ? grid_m : 8;
-    const int blk_n = grid_m <= 8 ? 1 : 4;
-    const int blocks_m = (grid_m + blk_m - 1) / blk_m;
-    const int blk = logical / (blk_m * blk_n), in_blk = logical % (blk_m * blk_n);
-    t.bm = (blk % blocks_m) * blk_m + in_blk % blk_m;
-    t.bn = (blk / blocks_m) * blk_n + in_blk / blk_m;
-    t.ok = t.bm < grid_m && t.bn < grid_n;
+    int r = item % n_tiles;
+    // column band
+    const int band_tiles = grid_m * 4, full_bands = grid_n / 4;
+    int band = r / band_tiles, width = 4;
+    if (band >= full_bands) {
+        band = full_bands;
+        width = grid_n - full_bands * 4;
+    }
+    r -= band * band_tiles;
+    // block of rows inside the band
+    const int full_blocks = grid_m / 8;
+    int blk = r / (8 * width), height = 8;
+    if (blk >= full_blocks) {
+        blk = full_blocks;
+        height = grid_m - full_blocks * 8;
+    }
+    r -= blk * 8 * width;
+    t.bm = blk * 8 + r % height;
+    t.bn = band * 4 + r / height;
+    t.ok = true;
     return t;
 }
 
@@ -1046,9 +1059,7 @@ template <int BM, int BN, int WM, int WN, int EPI, int SWIGLU, int DST = RPO_DMA
 hipError_t launch_one(const GemmArgs& a, int splits, void* out, hipStream_t s) {
     // direct-to-LDS pipeline shape: DBK-deep slabs in DST stages
     const int gm = ceil_div(a.M, BM), gn = ceil_div(a.N, BN);
-    // logical tile space padded to whole blocks of blk_m x blk_n tiles (see the kernel)
-    const int blk_m = gm < 8 ? gm : 8, blk_n = gm <= 8 ? 1 : 4;
-    const int n_tiles = ceil_div(gm, blk_m) * ceil_div(gn, blk_n) * blk_m * blk_n;
+    const int n_tiles = gm * gn;
     const int per_xcd = ceil_div(n_tiles * splits, kXcd);  // work items (tile, split) per XCD
     const int k_per_split = ceil_div(ceil_div(a.K, splits), kBK) * kBK;
     const dim3 grid((unsigned)(per_xcd * kXcd)), block(WM * WN * 64);
