@@ -735,7 +735,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const bf16* __res
         // accumulators go to LDS as fp32 [BM][BN + 1]; the rotation pairs (i, i + 64) of a row
         // then sit in one place whatever wave produced them.  q is rotated and stored to C, k is
         // rotated and stored to its page slot, v is stored transposed into its page.
-        static_assert(EPI != kEpiRope || (BN == 128 && WM == 1 && BM == 32 && NW == 4), "one head per tile");
+        static_assert(EPI != kEpiRope || (BN == 128 && WM == 1 && (BM == 32 || BM == 64) && NW == 4), "one head per tile");
         constexpr int LD = BN + 1;
         float* tile = (float*)smem_raw;
         int* row_pos = (int*)(tile + BM * LD);   // position, or -1: row beyond M / not active
@@ -744,7 +744,10 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const bf16* __res
         {
             const int col = wn * TN + (lane & 31), row_in = (lane >> 5) * 4;
 #pragma unroll
-            for (int e = 0; e < 16; ++e) tile[(8 * (e >> 2) + row_in + (e & 3)) * LD + col] = acc[0][0][e];
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    tile[(i * 32 + 8 * (e >> 2) + row_in + (e & 3)) * LD + col] = acc[i][0][e];
         }
         if (tid < BM) {
             const int r = m0 + tid;
@@ -998,9 +1001,11 @@ TileCfg pick_tile(const GemmArgs& a) {
     const int t256 = ceil_div(a.M, 256) * ceil_div(a.N, 256);
     // The gate/up projection of a decode step: one round of fewer 256x256 tiles than CUs; 256x192
     // tiles still fit one round and each is a quarter cheaper.
-    if (a.epilogue == kEpiSwiglu && a.M > 256 && t256 >= 128 && t256 <= 256 && a.K % kBK == 0 && a.path != 2 &&
+    if (a.epilogue == kEpiSwiglu && a.M > 128 && t256 >= 128 && t256 <= 256 && a.K % kBK == 0 && a.path != 2 &&
         (a.N / 2) % 16 == 0 && ceil_div(a.M, 256) * ceil_div(a.N, 192) <= 256)
         return TileCfg{kKidGemm256x192, 256, 192};
+    // up to 128 rows a 256-row tile multiplies mostly padding
+    if (a.epilogue == kEpiSwiglu && a.M > 64 && a.M <= 128 && t256 >= 128) return TileCfg{kKidGemm128, 128, 128};
     if (a.M > 512 || (a.M > 64 && t256 >= 128)) {
         // Workgroups run in rounds of one per CU.  A 256x192 tile costs about 0.78 of a 256x256
         // one; it wins when the wider tile would leave much of its last round idle (narrow N).
@@ -1012,7 +1017,8 @@ TileCfg pick_tile(const GemmArgs& a) {
     }
     if (a.K <= 4096 && a.K % kBK == 0 && a.epilogue != kEpiSwiglu && a.path != 2) {
         if (rope_direct(a)) return TileCfg{kKidGemm32, 32, 128};
-        return TileCfg{kKidGemm64x64, 64, 64};
+        // a single row of 64x64 tiles leaves most CUs idle once K is deep enough to split
+        if (a.M > 64 || a.K <= 2048 || a.ws == nullptr) return TileCfg{kKidGemm64x64, 64, 64};
     }
     if (a.M > 64) return TileCfg{kKidGemm128, 128, 128};
     return TileCfg{kKidGemm64, 64, 128};
@@ -1218,7 +1224,11 @@ static hipError_t launch_gemm_only(const GemmArgs& a, int splits, const TileCfg&
             if (deep_pipeline(a, t)) return launch_tile<128, 128, 2, 2, 4>(a, splits, s);
             return launch_tile<128, 128, 2, 2>(a, splits, s);
         case kKidGemm32:
-            if (rope_direct(a)) return launch_one<32, 128, 1, 4, kEpiRope, false, 4>(a, 1, a.C, s);
+            if (rope_direct(a)) {
+                // one round of workgroups: 64-row tiles once the 32-row ones outnumber the CUs
+                if (ceil_div(a.M, 32) * (a.N / 128) > 256) return launch_one<64, 128, 1, 4, kEpiRope, 0, 4>(a, 1, a.C, s);
+                return launch_one<32, 128, 1, 4, kEpiRope, 0, 4>(a, 1, a.C, s);
+            }
             return launch_tile<32, 128, 1, 4, 4>(a, splits, s);
         case kKidGemm64x64:
             return launch_tile<64, 64, 2, 2, 4>(a, splits, s);

@@ -208,6 +208,15 @@ def test_bf16_two_kv_heads_many_rollouts_mfma(rpo):
     run_case(rpo, BF16_2KV, p, a, m, G=16, max_rows=300, abs_tol=False)
 
 
+def test_bf16_many_rows_wide_rotary_tile(rpo):
+    """528 rollouts x 16 heads: more 32-row tiles than CUs, so the QKV projection of a decode step
+    takes its 64-row tiles (rotation and KV page write in the epilogue), with a ragged last tile."""
+    ng = 33
+    lens = tuple(20 + (5 * k) % 23 for k in range(ng))
+    p, a, m = bf16_workload(BF16_2KV, lens=lens, ms=(2,) * ng, seed=5)
+    run_case(rpo, BF16_2KV, p, a, m, G=16, abs_tol=False)
+
+
 def test_7b_shape_two_layers(rpo):
     """The 7B configuration's widths (d 3584, 28 q / 4 kv heads, F 18944, V 152064) on two layers:
     the projections take the tile shapes they take in the 7B benchmark (K = 3584 narrow tiles,
