@@ -91,16 +91,18 @@ __device__ inline float4 load4(const float* z, int i, int V, bool vec) {
     return r;
 }
 
-// One workgroup (4 waves) per output row.  The row is cut into segments of 1024 logits =
-// 4 sub-blocks of 256 (4 per lane); wave w owns segments w, w + 4, ...  Integer sums make
+// One workgroup (NW waves) per output row.  The row is cut into segments of 1024 logits =
+// 4 sub-blocks of 256 (4 per lane); wave w owns segments w, w + NW, ...  Integer sums make
 // the result independent of this decomposition.
 constexpr int kSubLen = 256;
 constexpr int kSegLen = 1024;
 constexpr int kMaxSeg = 256;  // vocab <= 262144
 
-__global__ __launch_bounds__(256) void sample_kernel(SampleArgs a) {
+// NW waves per row: few rows need many waves each to keep the vector ALUs busy.
+template <int NW>
+__global__ __launch_bounds__(NW * 64) void sample_kernel(SampleArgs a) {
     __shared__ uint64_t seg_sum[kMaxSeg];
-    __shared__ float red[4];
+    __shared__ float red[NW];
     __shared__ int pick_seg;
     __shared__ uint64_t pick_rem, row_total;
     const int r = blockIdx.x;
@@ -122,14 +124,16 @@ __global__ __launch_bounds__(256) void sample_kernel(SampleArgs a) {
     if (a.row_max) {  // the caller (the LM-head epilogue) already knows the row's maximum
         zmax = a.row_max[src];
     } else {
-        for (int i = tid * 4; i < V; i += 1024) {
+        for (int i = tid * 4; i < V; i += NW * 256) {
             const float4 v = load4(z, i, V, vec);
             zmax = fmaxf(fmaxf(zmax, fmaxf(v.x, v.y)), fmaxf(v.z, v.w));
         }
         zmax = wave_max(zmax);
         if (lane == 0) red[wave] = zmax;
         __syncthreads();
-        zmax = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+        zmax = red[0];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) zmax = fmaxf(zmax, red[w]);
     }
 
     // The logits of the wave's next segment are loaded while the weights of the current one are
@@ -137,11 +141,11 @@ __global__ __launch_bounds__(256) void sample_kernel(SampleArgs a) {
     float4 cur[4], nxt[4];
 #pragma unroll
     for (int sb = 0; sb < 4; ++sb) cur[sb] = load4(z, wave * kSegLen + sb * kSubLen + lane * 4, V, vec);
-    for (int sg = wave; sg < n_seg; sg += 4) {
-        const bool more = sg + 4 < n_seg;  // wave-uniform
+    for (int sg = wave; sg < n_seg; sg += NW) {
+        const bool more = sg + NW < n_seg;  // wave-uniform
         if (more) {
 #pragma unroll
-            for (int sb = 0; sb < 4; ++sb) nxt[sb] = load4(z, (sg + 4) * kSegLen + sb * kSubLen + lane * 4, V, vec);
+            for (int sb = 0; sb < 4; ++sb) nxt[sb] = load4(z, (sg + NW) * kSegLen + sb * kSubLen + lane * 4, V, vec);
         }
         uint64_t q = 0;  // < 16 * 2^41
 #pragma unroll
@@ -232,7 +236,11 @@ __global__ __launch_bounds__(256) void sample_kernel(SampleArgs a) {
 hipError_t launch_sample(const SampleArgs& a, hipStream_t s) {
     if (a.n_out_rows <= 0) return hipSuccess;
     if (a.vocab > kSegLen * kMaxSeg) return hipErrorInvalidValue;
-    sample_kernel<<<a.n_out_rows, 256, 0, s>>>(a);
+    // up to ~4 rows per CU: 16 waves per row (the sweep is ALU work, 27 operations per logit)
+    if (a.n_out_rows <= 1024)
+        sample_kernel<16><<<a.n_out_rows, 1024, 0, s>>>(a);
+    else
+        sample_kernel<4><<<a.n_out_rows, 256, 0, s>>>(a);
     return hipGetLastError();
 }
 
