@@ -267,6 +267,50 @@ def test_bf16_wide_vocab_fused_logprobs(rpo):
     assert np.max(np.abs(outs[0][ok] - outs[1][ok])) < 2e-2
 
 
+def test_logprob_pass_full_reprefill_on_a_g1_batch(rpo):
+    """The log-prob pass that re-prefills every sequence on its own (no sharing: a batch created
+    with G = 1, the way the 7B log-prob benchmark calls it) against the oracle, and against the
+    same sequences scored through shared prefixes (G = 3 rollouts per prefix)."""
+    mcfg = BF16_SMALL
+    rng = np.random.default_rng(21)
+    w = synth.perturb_gains(synth.make_weights(mcfg, seed=77))
+    w_np = synth.weights_to_numpy(w)
+    shape, shape_q = util.oracle_shape(mcfg), util.oracle_shape(mcfg, storage="model")
+    model = rpo.rpo_model_create(mcfg, util.to_device(w))
+    G, pre_lens, ms = 3, (150, 64, 97), (11, 7, 4)          # suffix lengths in descending order
+    prefixes = [rng.integers(0, mcfg.vocab, size=n).astype(np.int32) for n in pre_lens]
+    suffixes = [[rng.integers(0, mcfg.vocab, size=m).astype(np.int32) for _ in range(G)] for m in ms]
+    temp = 1.3
+
+    def score(n_groups, g_per, prefix_list, suffix_list):
+        cu_p = np.concatenate([[0], np.cumsum([len(x) for x in prefix_list])]).astype(np.int32)
+        cu_s = np.concatenate([[0], np.cumsum([len(x) for x in suffix_list])]).astype(np.int32)
+        batch = rpo.rpo_batch_create(model, n_groups, g_per, int(max(np.diff(cu_p))), max(ms), 64, 512)
+        last = torch.empty(n_groups, mcfg.vocab, device="cuda")
+        rpo.rpo_prefill_prefix(batch, torch.from_numpy(np.concatenate(prefix_list)).cuda(), cu_p, last)
+        rpo.rpo_kv_fork(batch)
+        out = torch.full((int(cu_s[-1]),), 9.0, dtype=torch.float32, device="cuda")
+        rpo.rpo_suffix_logprobs(batch, torch.from_numpy(np.concatenate(suffix_list)).cuda(), cu_s, temp, out)
+        torch.cuda.synchronize()
+        return out.cpu().numpy(), cu_s
+
+    flat_suffixes = [sfx for grp in suffixes for sfx in grp]
+    shared, cu_s = score(len(prefixes), G, prefixes, flat_suffixes)
+    own, cu_s1 = score(len(prefixes) * G, 1, [prefixes[k // G] for k in range(len(prefixes) * G)], flat_suffixes)
+    np.testing.assert_array_equal(cu_s, cu_s1)
+    worst, floor_max = 0.0, 0.0
+    for k, sfx in enumerate(flat_suffixes):
+        ref = T.suffix_logprobs(shape, w_np, prefixes[k // G], sfx, temp)
+        ref_q = T.suffix_logprobs(shape_q, w_np, prefixes[k // G], sfx, temp)
+        floor_max = max(floor_max, float(np.max(np.abs(ref_q - ref))))
+        for got in (shared, own):
+            worst = max(worst, float(np.max(np.abs(got[cu_s[k]:cu_s[k + 1]] - ref))))
+    tol = max(TOL["bf16"], 2.5 * floor_max)
+    print(f"log-probs vs oracle: max {worst:.3e} (bf16 storage floor max {floor_max:.3e})", flush=True)
+    assert worst < tol
+    assert np.max(np.abs(shared - own)) < tol            # two routes to the same numbers
+
+
 @pytest.mark.parametrize("mcfg,rows_per_group", [(BF16_WIDE_VOCAB, 32), (BF16_SMALL, 4)])
 def test_decode_row_max_output(rpo, mcfg, rows_per_group):
     """rpo_decode_step's row maxima equal the maxima of the logits it returns, bit for bit: from the
