@@ -54,9 +54,69 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ 
     for (int c = threadIdx.x; c < d; c += 256) hr[c] = from_f32<T>(xr[c] * inv * to_f32<T>(gain[c]));
 }
 
+// One wave per row, the row held in registers (NV float4 per lane: d <= 256 NV, d a multiple of
+// 4): x is read once with 16-byte loads, h leaves in 8- / 16-byte stores, no LDS.
+template <typename T, int NV>
+__global__ __launch_bounds__(256) void rmsnorm_wave_kernel(const float* __restrict__ x,
+                                                           const int32_t* __restrict__ row_idx,
+                                                           const T* __restrict__ gain, int d, float eps,
+                                                           T* __restrict__ h, int rows) {
+    const int lane = threadIdx.x & 63;
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= rows) return;
+    const int64_t src = row_idx ? row_idx[r] : r;
+    const float4* xr = (const float4*)(x + src * d);
+    const int nv = d >> 2;
+    float4 v[NV];
+    float ss = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int c = i * 64 + lane;
+        v[i] = c < nv ? xr[c] : float4{0.f, 0.f, 0.f, 0.f};
+        ss += (v[i].x * v[i].x + v[i].y * v[i].y) + (v[i].z * v[i].z + v[i].w * v[i].w);
+    }
+    ss = wave_sum(ss);
+    const float inv = 1.0f / sqrtf(ss / (float)d + eps);
+    T* hr = h + (int64_t)r * d;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int c = i * 64 + lane;
+        if (c >= nv) continue;
+        T g4[4], o4[4];
+        if constexpr (sizeof(T) == 2)
+            *(uint2*)g4 = *(const uint2*)(gain + 4 * c);
+        else
+            *(float4*)g4 = *(const float4*)(gain + 4 * c);
+        o4[0] = from_f32<T>(v[i].x * inv * to_f32<T>(g4[0]));
+        o4[1] = from_f32<T>(v[i].y * inv * to_f32<T>(g4[1]));
+        o4[2] = from_f32<T>(v[i].z * inv * to_f32<T>(g4[2]));
+        o4[3] = from_f32<T>(v[i].w * inv * to_f32<T>(g4[3]));
+        if constexpr (sizeof(T) == 2)
+            *(uint2*)(hr + 4 * c) = *(const uint2*)o4;
+        else
+            *(float4*)(hr + 4 * c) = *(const float4*)o4;
+    }
+}
+
+template <typename T>
+static bool launch_rmsnorm_wave(const float* x, const int32_t* row_idx, const T* gain, int d, float eps, T* h,
+                                int rows, hipStream_t s) {
+    if (d % 4 != 0 || d > 4096 || (uintptr_t)x % 16 != 0 || (uintptr_t)gain % 16 != 0 || (uintptr_t)h % 16 != 0)
+        return false;
+    const int grid = ceil_div(rows, 4);
+    if (d <= 1536)
+        rmsnorm_wave_kernel<T, 6><<<grid, 256, 0, s>>>(x, row_idx, gain, d, eps, h, rows);
+    else
+        rmsnorm_wave_kernel<T, 16><<<grid, 256, 0, s>>>(x, row_idx, gain, d, eps, h, rows);
+    return true;
+}
+
 hipError_t launch_rmsnorm(const float* x, const int32_t* row_idx, const void* gain, int dtype, int d,
                           float eps, void* h, int rows, hipStream_t s) {
     if (rows <= 0) return hipSuccess;
+    if (dtype == kF32 ? launch_rmsnorm_wave<float>(x, row_idx, (const float*)gain, d, eps, (float*)h, rows, s)
+                      : launch_rmsnorm_wave<bf16>(x, row_idx, (const bf16*)gain, d, eps, (bf16*)h, rows, s))
+        return hipGetLastError();
     if (dtype == kF32)
         rmsnorm_kernel<float><<<rows, 256, 0, s>>>(x, row_idx, (const float*)gain, d, eps, (float*)h);
     else
