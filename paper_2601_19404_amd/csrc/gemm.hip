@@ -867,12 +867,20 @@ __global__ __launch_bounds__(256) void gemm_splitk_reduce_norm_kernel(const floa
         const int c = tid + i * 256;
         if (c < nvec) {
             float4 acc = xrow[c];
-            for (int z = 0; z < splits; ++z) {
-                const float4 p = prow[(z * plane >> 2) + c];
-                acc.x += p.x;
-                acc.y += p.y;
-                acc.z += p.z;
-                acc.w += p.w;
+            // eight partial sums are requested at a time, then added in split order
+            for (int z0 = 0; z0 < splits; z0 += 8) {
+                float4 p[8];
+#pragma unroll
+                for (int z = 0; z < 8; ++z)
+                    if (z0 + z < splits) p[z] = prow[((z0 + z) * plane >> 2) + c];
+#pragma unroll
+                for (int z = 0; z < 8; ++z)
+                    if (z0 + z < splits) {
+                        acc.x += p[z].x;
+                        acc.y += p[z].y;
+                        acc.z += p[z].z;
+                        acc.w += p[z].w;
+                    }
             }
             xrow[c] = acc;
             v[i] = acc;
