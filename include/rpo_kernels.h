@@ -63,7 +63,8 @@ int rpo_set_kernel_path(int path);
  *   1  <256,256,2,4> (prefill-sized problems and wide decode projections)
  *   2  <256,128,2,2> (only via rpo_set_kernel_path)
  *   3  <128,128,2,2> (decode-sized problems, deep K)   4  <64,128,1,2> (the same for M <= 64)
- *   5  <32,128,1,4> (decode QKV projection: rotary embedding and KV page write in the epilogue)
+ *   5  <32,128,1,4> / <64,128,1,4> (decode QKV projection: rotary embedding and KV page write in
+ *      the epilogue; 64 rows once the 32-row tiles would outnumber the CUs)
  *   6  <64,64,2,2> (decode-sized problems, shallow K, no K split)
  *      (all epilogues of a tile shape together; a K-split launch includes its reduction)
  *   11 <256,192,4,2> (large M with a narrow N: fewer idle CUs in the last round of workgroups)
