@@ -120,7 +120,8 @@ def test_gemm_rejects_bad_arguments(rpo):
 
 # ---------------------------------------------------------------------------
 @pytest.mark.parametrize("vocab,rows,temperature", [(512, 8, 1.0), (151936, 6, 1.0), (152064, 3, 0.7),
-                                                    (1000, 5, 0.7), (3, 4, 1.0), (257, 4, 2.5)])
+                                                    (1000, 5, 0.7), (3, 4, 1.0), (257, 4, 2.5),
+                                                    (2100, 1100, 1.0)])   # > 1024 rows: four waves per row
 def test_sampler_bit_exact(rpo, vocab, rows, temperature):
     rng = np.random.default_rng(vocab)
     z = (rng.normal(size=(rows, vocab)) * 0.8).astype(np.float32)
