@@ -75,7 +75,7 @@ def test_gemm_mfma_bf16_every_tile_shape(rpo, shape, path):
 
 @pytest.mark.parametrize("path,ws_mb", [(0, 0), (0, 64), (1, 0), (27, 0)])
 @pytest.mark.parametrize("M,F,K", [(512, 8960, 1536), (40, 1024, 768), (700, 256, 2048), (130, 96, 1024),
-                                   (300, 18944, 3584), (264, 8032, 512)])
+                                   (300, 18944, 3584), (264, 8032, 512), (100, 18944, 512), (200, 18944, 512)])
 def test_gemm_swiglu(rpo, M, F, K, path, ws_mb):
     """Fused gate/up projection: C = silu(A Wg^T) * (A Wu^T), W = [gate rows; up rows].  Path 27 forces
     the 256x192 tile (gate / up rows interleaved in blocks of 16), which path 0 picks for decode batches."""
