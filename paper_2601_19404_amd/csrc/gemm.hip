@@ -592,10 +592,16 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const bf16* __res
         const int piece = (lane % PIECES) ^ lds_swizzle<BK>(row);
         b_src[j] = W + (int64_t)weight_row<SWIGLU>(min(n0 + row, N - 1), F) * ldw + piece * 8 + k_begin;
     }
+    // Narrow tiles: many workgroups share each operand slab (all row tiles of a column tile read the
+    // same weight rows, all column tiles of a row tile the same activations).  Each workgroup walks
+    // K from its own starting slab, so that the workgroups running together ask the L2 for
+    // different lines instead of the same ones at the same time.
+    const int k_rot = (BM <= 64 && nk > 0) ? (tc.bm * 5 + tc.bn * 3) % nk : 0;
     // slab s_ (clamped to the last one: loads past the end are redundant, never read) -> stage
 #define RPO_DMA_SLAB(s_)                                                                                 \
     {                                                                                                    \
-        const int sl_ = (s_) < nk ? (s_) : nk - 1;                                                       \
+        int sl_ = ((s_) < nk ? (s_) : nk - 1) + k_rot;                                                   \
+        sl_ = sl_ >= nk ? sl_ - nk : sl_;                                                                \
         const int st_ = (s_) % STAGES;                                                                   \
         _Pragma("unroll") for (int j = 0; j < A_INST; ++j)                                               \
             dma_load16(a_src[j] + sl_ * BK, lds_a + (st_ * A_STAGE + (j * NW + wave) * 512) * 2);        \
