@@ -22,11 +22,11 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK = {"hbm": (8000.0, "GB/s"), "mfma": (2500.0, "TFLOP/s"), "alu": (157.3, "TFLOP/s")}
-# HBM-side bytes per launch of the dominant kernel's heaviest launch (prefill gate/up projection,
-# M=16384, N=17920, K=1536, SwiGLU epilogue), from two rocprofv3 --pmc runs (FETCH_SIZE x 2.0 and
-# WRITE_SIZE x 1.0 after calibration against a 1 GiB copy).
-GEMM256_TRAFFIC = dict(launch="prefill gate/up projection M=16384 N=17920 K=1536", read_bytes=1340.4e6,
-                       write_bytes=293.6e6, algorithmic_bytes=105.4e6 + 293.6e6)
+# HBM-side bytes per launch of the dominant kernel's heaviest launch (prefill gate/up projection of a
+# full chunk, M=32768, N=17920, K=1536, SwiGLU epilogue), from two rocprofv3 --pmc runs (FETCH_SIZE
+# x 2.0 and WRITE_SIZE x 1.0 after calibration against a 1 GiB copy).
+GEMM256_TRAFFIC = dict(launch="prefill gate/up projection M=32768 N=17920 K=1536", read_bytes=2680.3e6,
+                       write_bytes=587.7e6, algorithmic_bytes=155.7e6 + 587.2e6)
 KERNEL_BOUND = {"gemm256": "mfma", "gemm256x128": "mfma", "gemm256x192": "mfma", "gemm128": "mfma", "gemm64": "mfma",
                 "gemm32": "mfma", "gemm64x64": "mfma", "gemm_generic": "alu", "attn_chunk": "mfma",
                 "attn_decode": "hbm", "sample": "hbm"}
@@ -216,7 +216,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="C1", choices=["C0", "C1", "C2", "C3", "C4"])
     ap.add_argument("--groups", type=int, default=None, help="override the number of groups (debugging)")
-    ap.add_argument("--max-rows", type=int, default=16384)
+    ap.add_argument("--max-rows", type=int, default=32768,
+                    help="rows pushed through the layers at once (prefill and log-prob chunks of whole sequences)")
     ap.add_argument("--G", type=int, default=None, help="rollouts per group (paper: 6, 8, 16)")
     ap.add_argument("--temperature", type=float, default=None, help="sampling temperature (paper: 0.7)")
     ap.add_argument("--trunc-max", type=int, default=None,
