@@ -22,14 +22,70 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK = {"hbm": (8000.0, "GB/s"), "mfma": (2500.0, "TFLOP/s"), "alu": (157.3, "TFLOP/s")}
-# HBM-side bytes per launch of the dominant kernel's heaviest launch (prefill gate/up projection of a
-# full chunk, M=32768, N=17920, K=1536, SwiGLU epilogue), from two rocprofv3 --pmc runs (FETCH_SIZE
-# x 2.0 and WRITE_SIZE x 1.0 after calibration against a 1 GiB copy).
-GEMM256_TRAFFIC = dict(launch="prefill gate/up projection M=32768 N=17920 K=1536", read_bytes=2680.3e6,
-                       write_bytes=587.7e6, algorithmic_bytes=155.7e6 + 587.2e6)
-KERNEL_BOUND = {"gemm256": "mfma", "gemm256x128": "mfma", "gemm256x192": "mfma", "gemm128": "mfma", "gemm64": "mfma",
-                "gemm32": "mfma", "gemm64x64": "mfma", "gemm_generic": "alu", "attn_chunk": "mfma",
-                "attn_decode": "hbm", "sample": "hbm"}
+HBM_BPS, MFMA_FLOPS = 8.0e12, 2.5e15
+# HBM-side bytes of ONE launch of the dominant kernel (the gate/up projection of a full prefill chunk),
+# quoted from rocprofv3 --pmc runs of that launch alone (FETCH_SIZE, WRITE_SIZE scaled by what the
+# same counters read for a plain copy of known size): a stored figure, not something this run
+# measures -- the counters cannot be read from inside the timed run.  Source and command:
+# profiles/gemm_hbm_traffic_pmc.txt.
+DOMINANT_TRAFFIC = dict(launch="gate/up projection of a full chunk, M=32768 N=17920 K=1536, SwiGLU epilogue",
+                        read_bytes=2680.3e6, write_bytes=587.7e6, algorithmic_bytes=155.7e6 + 587.2e6,
+                        source="profiles/gemm_hbm_traffic_pmc.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
+KERNEL_BOUND = {"gemm256": "mfma", "gemm256_swiglu": "mfma", "gemm256x128": "mfma", "gemm256x192": "mfma",
+                "gemm128": "mfma", "gemm64": "mfma", "gemm32": "mfma", "gemm64x64": "mfma",
+                "gemm_generic": "alu", "attn_chunk": "mfma", "attn_decode": "hbm", "sample": "hbm"}
+
+
+def _model_sizes(mc):
+    es = 2 if mc.dtype == "bf16" else 4
+    proj = dict(qkv=mc.qkv_rows * mc.d_model, o=mc.d_model * mc.n_q_heads * mc.head_dim,
+                gate_up=2 * mc.d_ffn * mc.d_model, down=mc.d_model * mc.d_ffn)
+    io = dict(qkv=(mc.d_model, mc.qkv_rows), o=(mc.n_q_heads * mc.head_dim, mc.d_model),
+              gate_up=(mc.d_model, mc.d_ffn), down=(mc.d_ffn, mc.d_model))
+    return es, proj, io
+
+
+def step_roofline(st) -> dict:
+    """Lower bound of one pass at the published peaks: the sum over kernel classes k of
+    max(algorithmic bytes_k / 8 TB/s, algorithmic flops_k / 2.5 PFLOP/s), per phase (ms)."""
+    cfg, mc, m, G = st["cfg"], st["cfg"].model, st["m"], st["G"]
+    es, proj, io = _model_sizes(mc)
+    L, V, d, dh, Hq = mc.n_layers, mc.vocab, mc.d_model, mc.head_dim, mc.n_q_heads
+    kv_tok = 2 * mc.n_kv_heads * dh * es                      # one layer
+
+    def gemm_t(rows, params, k_in, n_out, out_es=None):
+        byt = params * es + rows * (k_in * es + n_out * (es if out_es is None else out_es))
+        return max(byt / HBM_BPS, 2.0 * rows * params / MFMA_FLOPS)
+
+    def layers_t(rows):
+        return L * sum(gemm_t(rows, proj[k], *io[k]) for k in proj)
+
+    S = np.asarray([cfg.prompt_len + cfg.traj_len - int(mk) for mk in m], np.float64)
+    # prefill: projections on every prefix row, causal attention, LM head on the last row of each group
+    pre = layers_t(float(S.sum()))
+    attn_fl = 4.0 * dh * Hq * L * float((S * (S + 1) / 2).sum())
+    attn_by = L * float(S.sum()) * (kv_tok + 2 * Hq * dh * es)
+    pre += max(attn_fl / MFMA_FLOPS, attn_by / HBM_BPS) + gemm_t(len(m), V * d, d, V, 4)
+    # decode: per step the projections on the live rows, the shared-prefix attention, LM head, sampler
+    dec = 0.0
+    for j in range(1, int(m.max())):
+        live = m > j
+        n = int(live.sum()) * G
+        if n == 0:
+            break
+        dec += layers_t(n) + gemm_t(n, V * d, d, V, 4)
+        a_by = L * kv_tok * (float(S[live].sum()) + n * (j + 1))
+        a_fl = 4.0 * dh * Hq * L * G * float((S[live] + j + 1).sum())
+        dec += max(a_by / HBM_BPS, a_fl / MFMA_FLOPS) + n * V * 4 / HBM_BPS
+    # first draw of every rollout reads the group's prefill logits row
+    dec += len(m) * G * V * 4 / HBM_BPS
+    # log-prob pass: rows 0..m-2 of every suffix through the layers, LM head on m rows per rollout
+    fr = np.maximum(m.astype(np.float64) - 1, 0)
+    lp = layers_t(float(fr.sum()) * G)
+    lp_fl = 4.0 * dh * Hq * L * G * float((fr * S + fr * (fr + 1) / 2).sum())
+    lp += lp_fl / MFMA_FLOPS + gemm_t(float(m.sum()) * G, V * d, d, 0)
+    return {"prefill+fork": pre * 1e3, "decode": dec * 1e3, "logprobs+advantages": lp * 1e3,
+            "total": (pre + dec + lp) * 1e3}
 
 
 def algorithmic_decode_bytes(st) -> float:
@@ -179,7 +235,6 @@ def cpu_baseline(st, budget_tokens: int = 6, prefix_cap: int = 256, n_rollouts: 
     """The fp64 oracle on the host cores, on a bounded slice of the same workload: group 0,
     its prefix cut to the last `prefix_cap` tokens, `n_rollouts` rollouts, `budget_tokens`
     regenerated tokens each."""
-    import torch
     from oracle import rollout as orollout
     from oracle import transformer as T
     from paper_2601_19404_amd import synth
@@ -203,7 +258,13 @@ def cpu_baseline(st, budget_tokens: int = 6, prefix_cap: int = 256, n_rollouts: 
                                   3, np.arange(n_rollouts), n_tokens=n_tok)
     dt = time.perf_counter() - t0
     gen = n_rollouts * n_tok
-    return dict(value=gen / dt, unit="tokens/s", cores=int(torch.get_num_threads()), kind="oracle",
+    try:
+        from threadpoolctl import threadpool_info
+        blas = max([p.get("num_threads", 1) for p in threadpool_info() if p.get("user_api") == "blas"] or [1])
+    except Exception:
+        blas = None
+    cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else os.cpu_count()
+    return dict(value=gen / dt, unit="tokens/s", cores=int(cores), blas_threads=blas, kind="oracle",
                 sample=(f"group 0 of {st['cfg'].name}, prefix cut to its last {len(out['prefix'])} tokens, "
                         f"{n_rollouts} rollouts x {n_tok} regenerated tokens, {dt:.1f} s of fp64 numpy"),
                 seconds=dt)
@@ -222,17 +283,10 @@ def main():
     ap.add_argument("--temperature", type=float, default=None, help="sampling temperature (paper: 0.7)")
     ap.add_argument("--trunc-max", type=int, default=None,
                     help="draw m ~ U{0..L} as in Eq. 3 (paper: L = 300, 500, 800) instead of the 5-10 %% cut")
-    ap.add_argument("--profile-every", type=int, default=8,
-                    help="bracket every n-th launch of the profiled kernel with HIP events (1 = all)")
-    ap.add_argument("--profile-kernel", default="gemm256",
-                    help="kernel whose launches are timed with HIP events for the roofline object")
+    ap.add_argument("--profile-kernel", default="gemm256_swiglu",
+                    help="kernel whose launches are ALL timed with HIP events for the roofline object "
+                         "(default: the instantiation that leads the kernel table of a step by time)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--gemm-probe", default=None, metavar="M,N,K,EPI",
-                    help="only run the MFMA GEMM five times on one shape (bf16, N(0,1) inputs; EPI as in "
-                         "rpo_gemm_nt) so that rocprofv3 --pmc can read its HBM traffic, and exit")
-    ap.add_argument("--copy-probe", action="store_true",
-                    help="only copy 1 GiB device to device three times (calibrates the FETCH_SIZE / "
-                         "WRITE_SIZE counters of a rocprofv3 --pmc run) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1",
@@ -245,26 +299,6 @@ def main():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
     rpo.lib()
-    if args.copy_probe:
-        a = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
-        b = torch.empty_like(a)
-        for _ in range(3):
-            b.copy_(a)
-        torch.cuda.synchronize()
-        print(json.dumps({"copy_probe_bytes_each_way": a.numel() * 4}))
-        return
-    if args.gemm_probe:
-        M, N, K, epi = (int(v) for v in args.gemm_probe.split(","))
-        a = torch.randn(M, K, device="cuda").to(torch.bfloat16)
-        w = (torch.randn(N, K, device="cuda") * 0.02).to(torch.bfloat16)
-        c = torch.zeros(M, N // 2 if epi == 3 else N, device="cuda",
-                        dtype=torch.bfloat16 if epi in (0, 3) else torch.float32)
-        ws = torch.empty(96 << 20, dtype=torch.uint8, device="cuda")
-        for _ in range(5):
-            rpo.rpo_gemm_nt(a, w, c, epi, ws)
-        torch.cuda.synchronize()
-        print(json.dumps({"gemm_probe": [M, N, K, epi]}))
-        return
     if args.workload == "C4":
         run_c4(args)
         return
@@ -274,11 +308,15 @@ def main():
         one_step(st, seed=100 + i)
     torch.cuda.synchronize()
 
-    kid = rpo.KERNEL_IDS[args.profile_kernel]
-    # every 8th launch is bracketed by events (the stride is coprime to the 29 launches of this
-    # kernel per decode step, so every projection is sampled evenly): bracketing all ~5000
-    # launches per step costs about 2 % of the step
-    rpo.rpo_profile_start(kid, args.profile_every)
+    # HIP events (recorded by the library on the launch stream) around EVERY launch of the dominant
+    # kernel, and around every 5th decode-attention launch (5 is coprime to the 28 launches per
+    # step, so all layers are sampled evenly) and every sampler launch: a few thousand event pairs
+    # per step, under 1 % of its time.
+    timed = {args.profile_kernel: 1}
+    for name, every in (("attn_decode", 5), ("sample", 1)):
+        timed.setdefault(name, every)
+    for name, every in timed.items():
+        rpo.rpo_profile_start(rpo.KERNEL_IDS[name], every)
     t0 = time.perf_counter()
     all_marks = []
     for i in range(args.steps):
@@ -292,25 +330,33 @@ def main():
         for (_, e0, c0), (name, e1, c1) in zip(marks[:-1], marks[1:]):
             phases[name] = phases.get(name, 0.0) + e0.elapsed_time(e1) / args.steps
             enqueue[name] = enqueue.get(name, 0.0) + (c1 - c0) * 1e3 / args.steps
-    launches, k_ms, k_flops, k_bytes = rpo.rpo_profile_stop()
+
+    def kernel_report(name):
+        launches, k_ms, k_flops, k_bytes = rpo.rpo_profile_stop(rpo.KERNEL_IDS[name])
+        bound = KERNEL_BOUND.get(name, "hbm")
+        peak, unit = PEAK[bound]
+        work = k_bytes / 1e9 if bound == "hbm" else k_flops / 1e12
+        achieved = work / (k_ms / 1e3) if launches and k_ms > 0 else 0.0
+        every = timed[name]
+        return dict(bound=bound, achieved=achieved, peak=peak, unit=unit, frac=achieved / peak,
+                    kernel=name, launches_timed=launches, timed_every_nth_launch=every,
+                    avg_launch_us=(k_ms * 1e3 / launches) if launches else None,
+                    share_of_step_time=(k_ms * every / 1e3) / dt)
+
+    roofline = kernel_report(args.profile_kernel)
+    others = {name: kernel_report(name) for name in timed if name != args.profile_kernel}
+    roofline["traffic"] = None
+    if args.profile_kernel == "gemm256_swiglu" and args.workload == "C1":
+        roofline["traffic"] = DOMINANT_TRAFFIC["read_bytes"] + DOMINANT_TRAFFIC["write_bytes"]
+        roofline["traffic_of"] = DOMINANT_TRAFFIC
+    roofline["other_kernels"] = others
 
     n_gen = res.n_generated
     value = n_gen * args.steps / dt
-    bound = KERNEL_BOUND.get(args.profile_kernel, "hbm")
-    peak, unit = PEAK[bound]
-    if launches and k_ms > 0:
-        work = k_bytes / 1e9 if bound == "hbm" else k_flops / 1e12
-        achieved = work / (k_ms / 1e3)
-    else:
-        achieved = 0.0
-    traffic = None
-    if args.profile_kernel == "gemm256" and args.workload == "C1":
-        traffic = GEMM256_TRAFFIC["read_bytes"] + GEMM256_TRAFFIC["write_bytes"]
-    roofline = dict(bound=bound, achieved=achieved, peak=peak, unit=unit, frac=achieved / peak, traffic=traffic,
-                    traffic_of=GEMM256_TRAFFIC if traffic else None,
-                    kernel=args.profile_kernel, launches=launches, timed_every_nth_launch=args.profile_every,
-                    avg_launch_us=(k_ms * 1e3 / launches) if launches else None,
-                    share_of_step_time=(k_ms * args.profile_every / 1e3) / dt)  # estimate: timed launches x stride
+    rollout_ms = phases.get("prefill+fork", float("nan")) + phases.get("decode", float("nan"))
+    dec_bytes = algorithmic_decode_bytes(st)
+    dec_s = phases.get("decode", float("nan")) / 1e3
+    bound_ms = step_roofline(st)
     out = dict(metric="suffix-rollout tokens/sec at 1.5B shape; decode HBM GB/s vs peak",
                value=value, unit="tokens/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
                ms_per_step=dt * 1e3 / args.steps, higher_is_better=True, scaling="weak", vs_baseline=None,
@@ -319,14 +365,19 @@ def main():
                            prompt_len=cfg.prompt_len, traj_len=cfg.traj_len,
                            suffix_len_range=[int(st["m"].min()), int(st["m"].max())],
                            generated_tokens_per_step=int(n_gen), page_tokens=st["page"],
-                           temperature=cfg.temperature, mean_suffix_len=float(st["m"].mean())),
+                           temperature=cfg.temperature, mean_suffix_len=float(st["m"].mean()),
+                           step="cut+pack, prefill, fork, sample/decode loop, suffix log-probs, advantages"),
                phase_ms_per_step={k: round(v, 2) for k, v in phases.items()},
                host_enqueue_ms_per_step={k: round(v, 2) for k, v in enqueue.items()},
-               decode_tokens_per_s=(n_gen - st["ng"] * st["G"]) / (phases.get("decode", float("nan")) / 1e3),
-               decode_hbm=dict(algorithmic_GB_per_step=round(algorithmic_decode_bytes(st) / 1e9, 2),
-                               achieved_GBps=algorithmic_decode_bytes(st) / 1e9 / (phases.get("decode", float("nan")) / 1e3),
-                               peak_GBps=8000.0,
-                               frac=algorithmic_decode_bytes(st) / 1e9 / (phases.get("decode", float("nan")) / 1e3) / 8000.0),
+               # the rollout alone (prefill + fork + decode loop + sampling), without the log-prob pass
+               rollout_tokens_per_s=n_gen / (rollout_ms / 1e3),
+               decode_tokens_per_s=(n_gen - st["ng"] * st["G"]) / dec_s,
+               decode_hbm=dict(algorithmic_GB_per_step=round(dec_bytes / 1e9, 2),
+                               achieved_GBps=dec_bytes / 1e9 / dec_s, peak_GBps=8000.0,
+                               frac=dec_bytes / 1e9 / dec_s / 8000.0),
+               step_roofline_ms={k: round(v, 2) for k, v in bound_ms.items()},
+               frac_of_step_roofline={k: round(bound_ms[k] / v, 3) for k, v in
+                                      list(phases.items()) + [("total", dt * 1e3 / args.steps)] if k in bound_ms},
                roofline=roofline)
     # what this GPU sustains on a plain copy and on an MFMA issue loop, measured now (outside the
     # timed region): context for the fractions above, which are against the published peaks
@@ -335,8 +386,8 @@ def main():
         out["practical_peaks"] = dict(copy_GBps=round(copy_gbps, 1), mfma_bf16_TFLOPs=round(mfma_tflops, 1),
                                       note="plain copy (read + write) and bf16 32x32x16 MFMA issue loop, "
                                            "measured by rpo_probe_peaks in this run")
-        practical = mfma_tflops if bound == "mfma" else copy_gbps if bound == "hbm" else 0.0
-        roofline["frac_of_practical"] = achieved / practical if practical > 0 else None
+        practical = mfma_tflops if roofline["bound"] == "mfma" else copy_gbps if roofline["bound"] == "hbm" else 0.0
+        roofline["frac_of_practical"] = roofline["achieved"] / practical if practical > 0 else None
     except rpo.RpoError as e:  # the probe is informational
         out["practical_peaks"] = dict(error=str(e))
     if not args.no_cpu_baseline:

@@ -52,15 +52,18 @@ int rpo_probe_peaks(const void *src_dev, void *dst_dev, size_t bytes, float *scr
  * Errors: RPO_EINVAL. */
 int rpo_set_kernel_path(int path);
 
-/* Per-kernel timing for roofline reports.  rpo_profile_start(kernel_id) makes every later
- * launch of that kernel (process-wide, any stream) bracketed by a pair of HIP events recorded
- * on the launch stream; rpo_profile_stop waits for the last event and returns the number of
- * launches, the summed event time in milliseconds, and the summed ALGORITHMIC flops and bytes
- * of those launches as the library counts them (GEMM: 2MNK flops, operands + result bytes;
- * decode attention: K/V bytes with a group's shared prefix counted once per group; sampler:
- * the logits rows read once).  Kernel ids:
+/* Per-kernel timing for roofline reports.  rpo_profile_start(kernel_id, every) makes every
+ * `every`-th later launch of that kernel (the 1st, the every+1-th, ...; process-wide, any stream)
+ * bracketed by a pair of HIP events recorded on the launch stream; several kernel ids may be
+ * timed at once.  rpo_profile_stop(kernel_id, ...) waits for that kernel's last event and returns
+ * the number of bracketed launches, their summed event time in milliseconds, and their summed
+ * ALGORITHMIC flops and bytes as the library counts them (GEMM: 2MNK flops, operands + result
+ * bytes; decode attention: K/V bytes with a group's shared prefix counted once per group;
+ * sampler: the logits rows read once).  Kernel ids:
  * (MFMA GEMM tile shapes <BM, BN, waves along M, waves along N>)
- *   1  <256,256,2,4> (prefill-sized problems and wide decode projections)
+ *   1  <256,256,2,4> (prefill-sized problems and wide decode projections), every epilogue but SwiGLU
+ *   12 <256,256,2,4> with the fused SwiGLU epilogue: the gate/up projection of prefill and
+ *      log-prob chunks, one instantiation, the heaviest kernel of a rollout step
  *   2  <256,128,2,2> (only via rpo_set_kernel_path)
  *   3  <128,128,2,2> (decode-sized problems, deep K)   4  <64,128,1,2> (the same for M <= 64)
  *   5  <32,128,1,4> / <64,128,1,4> (decode QKV projection: rotary embedding and KV page write in
@@ -70,15 +73,13 @@ int rpo_set_kernel_path(int path);
  *   11 <256,192,4,2> (large M with a narrow N: fewer idle CUs in the last round of workgroups)
  *   7  gemm_generic_kernel      8  attn_decode_mfma_kernel (+ merge)   9  attn_chunk_mfma_kernel
  *   10 sample_kernel
- * Host-side only (event create / record / synchronise); not thread-safe.
- * Errors: RPO_EINVAL (unknown id, NULL), RPO_EHIP. */
-int rpo_profile_start(int kernel_id);
-/* The same, but only every `every`-th launch of the kernel (the 1st, the every+1-th, ...) is
- * bracketed and counted: event pairs around each of thousands of short launches would slow the
- * run that is being measured.  rpo_profile_stop then reports the bracketed launches only (their
- * number, time, flops and bytes).  Errors: RPO_EINVAL (unknown id, every < 1). */
-int rpo_profile_start_sampled(int kernel_id, int every);
-int rpo_profile_stop(int64_t *n_launches, double *total_ms, double *total_flops, double *total_bytes);
+ * The timing state and rpo_set_kernel_path's switch are process-wide and unsynchronised: use them
+ * from the one thread that issues the compute calls, and not while another thread is inside one.
+ * Host-side only (event create / record / synchronise).
+ * Errors: RPO_EINVAL (unknown id, every < 1, NULL), RPO_EHIP. */
+int rpo_profile_start(int kernel_id, int every);
+int rpo_profile_stop(int kernel_id, int64_t *n_launches, double *total_ms, double *total_flops,
+                     double *total_bytes);
 
 #ifdef __cplusplus
 }

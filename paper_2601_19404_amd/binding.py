@@ -75,13 +75,12 @@ def lib() -> C.CDLL:
     L.rpo_gemm_nt.argtypes = [vp, i64, vp, i64, vp, i64, i32, i32, i32, i32, i32, vp, sz, vp]
     L.rpo_probe_peaks.argtypes = [vp, vp, sz, vp, C.POINTER(C.c_double), C.POINTER(C.c_double), vp]
     L.rpo_set_kernel_path.argtypes = [C.c_int]
-    L.rpo_profile_start.argtypes = [C.c_int]
-    L.rpo_profile_start_sampled.argtypes = [C.c_int, C.c_int]
-    L.rpo_profile_stop.argtypes = [C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double),
+    L.rpo_profile_start.argtypes = [C.c_int, C.c_int]
+    L.rpo_profile_stop.argtypes = [C.c_int, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double),
                                    C.POINTER(C.c_double)]
     for name in ("rpo_model_create", "rpo_batch_create", "rpo_prefill_prefix", "rpo_kv_fork",
                  "rpo_decode_step", "rpo_sample", "rpo_suffix_logprobs", "grpo_advantages",
-                 "rpo_shape_rewards", "rpo_objective_forward", "rpo_gemm_nt", "rpo_set_kernel_path", "rpo_profile_start", "rpo_profile_start_sampled", "rpo_profile_stop", "rpo_probe_peaks"):
+                 "rpo_shape_rewards", "rpo_objective_forward", "rpo_gemm_nt", "rpo_set_kernel_path", "rpo_profile_start", "rpo_profile_stop", "rpo_probe_peaks"):
         getattr(L, name).restype = C.c_int
     _lib = L
     return L
@@ -91,7 +90,7 @@ EXPORTS = ("rpo_model_create", "rpo_model_destroy", "rpo_kv_pool_bytes", "rpo_wo
            "rpo_batch_create", "rpo_batch_destroy", "rpo_prefill_prefix", "rpo_kv_fork",
            "rpo_decode_step", "rpo_sample", "rpo_suffix_logprobs", "grpo_advantages",
            "rpo_shape_rewards", "rpo_objective_forward", "rpo_last_error", "rpo_gemm_nt", "rpo_set_kernel_path", "rpo_profile_start",
-           "rpo_profile_start_sampled", "rpo_profile_stop", "rpo_probe_peaks")
+           "rpo_profile_stop", "rpo_probe_peaks")
 
 
 def _check(code: int) -> None:
@@ -333,17 +332,18 @@ def rpo_probe_peaks(n_bytes: int = 1 << 30, stream=None):
     return gbps.value, tflops.value
 
 
-KERNEL_IDS = {"gemm256": 1, "gemm256x128": 2, "gemm128": 3, "gemm64": 4, "gemm32": 5, "gemm64x64": 6, "gemm_generic": 7, "gemm256x192": 11,
-              "attn_decode": 8, "attn_chunk": 9, "sample": 10}
+KERNEL_IDS = {"gemm256": 1, "gemm256x128": 2, "gemm128": 3, "gemm64": 4, "gemm32": 5, "gemm64x64": 6,
+              "gemm_generic": 7, "gemm256x192": 11, "attn_decode": 8, "attn_chunk": 9, "sample": 10,
+              "gemm256_swiglu": 12}
 
 
 def rpo_profile_start(kernel_id: int, every: int = 1) -> None:
     """Bracket every `every`-th launch of the kernel with HIP events until rpo_profile_stop."""
-    _check(lib().rpo_profile_start_sampled(kernel_id, every))
+    _check(lib().rpo_profile_start(kernel_id, every))
 
 
-def rpo_profile_stop():
-    """-> (launches, total_ms, total_flops, total_bytes) of the kernel chosen at start."""
+def rpo_profile_stop(kernel_id: int):
+    """-> (launches, total_ms, total_flops, total_bytes) of the bracketed launches of that kernel."""
     n, ms, fl, by = C.c_int64(), C.c_double(), C.c_double(), C.c_double()
-    _check(lib().rpo_profile_stop(C.byref(n), C.byref(ms), C.byref(fl), C.byref(by)))
+    _check(lib().rpo_profile_stop(kernel_id, C.byref(n), C.byref(ms), C.byref(fl), C.byref(by)))
     return n.value, ms.value, fl.value, by.value

@@ -380,7 +380,7 @@ __global__ __launch_bounds__(256) void attn_decode_mfma_kernel(AttnArgs a, Decod
     } else {
         ri = part - n_pref;
         col_ok = col < hpk;
-        wave_live = wave == 0;
+        wave_live = wave * 16 < hpk;  // up to 64 query heads per KV head: one 16-column tile per wave
         page_begin = n_shared;
         page_end = n_shared;  // extended below if the rollout is alive
         piece = dg.n_split;

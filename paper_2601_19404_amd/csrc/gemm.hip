@@ -1225,7 +1225,9 @@ int gemm_fuses_max(const GemmArgs& a) {
 
 int gemm_kernel_id(const GemmArgs& a) {
     if (!mfma_ok(a)) return kKidGemmGeneric;
-    return pick_tile(a).id;
+    const int id = pick_tile(a).id;
+    // the heaviest instantiation of a rollout step is reported on its own
+    return (id == kKidGemm256 && a.epilogue == kEpiSwiglu) ? (int)kKidGemm256Swiglu : id;
 }
 
 static hipError_t launch_gemm_only(const GemmArgs& a, int splits, const TileCfg& t, hipStream_t s) {

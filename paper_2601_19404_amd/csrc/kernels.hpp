@@ -98,7 +98,8 @@ enum KernelId : int {
     kKidAttnDecode = 8,     // attn_decode_mfma_kernel
     kKidAttnChunk = 9,      // attn_chunk_mfma_kernel
     kKidSample = 10,        // sample_kernel
-    kKidCount = 12,
+    kKidGemm256Swiglu = 12, // <256,256,2,4> with the fused SwiGLU epilogue (gate/up of prefill / log-prob chunks)
+    kKidCount = 13,
 };
 // Which kernel launch_gemm picks for these arguments.
 int gemm_kernel_id(const GemmArgs& a);

@@ -58,11 +58,11 @@ extern "C" int rpo_set_kernel_path(int path) {
 }
 
 // ---------------------------------------------------------------------------
-// per-kernel timing: HIP event pairs around every launch of one chosen kernel
+// per-kernel timing: HIP event pairs around the launches of chosen kernels
 // ---------------------------------------------------------------------------
 namespace {
 struct Profile {
-    int kernel_id = 0;
+    bool on = false;
     std::vector<hipEvent_t> events;  // pool, reused across sessions
     size_t used = 0;
     double flops = 0.0, bytes = 0.0;
@@ -78,57 +78,60 @@ struct Profile {
         return hipEventRecord(events[used++], s);
     }
 };
-Profile g_prof;
+Profile g_prof[kKidCount];  // one slot per kernel id; several may be active at once
 
-// Runs `launch` and, when kernel `id` is the one being timed, brackets it with events.
+// Runs `launch` and, when kernel `id` is being timed, brackets it with events.
 template <typename F>
 hipError_t timed(int id, double flops, double bytes, hipStream_t s, F&& launch) {
-    const bool on = id != 0 && id == g_prof.kernel_id && (g_prof.seen++ % g_prof.every) == 0;
+    Profile& p = g_prof[(id > 0 && id < kKidCount) ? id : 0];
+    const bool on = p.on && (p.seen++ % p.every) == 0;
     if (on) {
-        hipError_t e = g_prof.mark(s);
+        hipError_t e = p.mark(s);
         if (e != hipSuccess) return e;
     }
     hipError_t e = launch();
     if (e != hipSuccess) return e;
     if (on) {
-        e = g_prof.mark(s);
-        g_prof.flops += flops;
-        g_prof.bytes += bytes;
+        e = p.mark(s);
+        p.flops += flops;
+        p.bytes += bytes;
     }
     return e;
 }
 }  // namespace
 
-extern "C" int rpo_profile_start_sampled(int kernel_id, int every) {
+extern "C" int rpo_profile_start(int kernel_id, int every) {
     if (kernel_id <= 0 || kernel_id >= kKidCount) return fail(RPO_EINVAL, "rpo_profile_start: unknown kernel id");
-    if (every < 1) return fail(RPO_EINVAL, "rpo_profile_start_sampled: every must be >= 1");
-    g_prof.kernel_id = kernel_id;
-    g_prof.used = 0;
-    g_prof.flops = g_prof.bytes = 0.0;
-    g_prof.every = every;
-    g_prof.seen = 0;
+    if (every < 1) return fail(RPO_EINVAL, "rpo_profile_start: every must be >= 1");
+    Profile& p = g_prof[kernel_id];
+    p.on = true;
+    p.used = 0;
+    p.flops = p.bytes = 0.0;
+    p.every = every;
+    p.seen = 0;
     return RPO_OK;
 }
 
-extern "C" int rpo_profile_start(int kernel_id) { return rpo_profile_start_sampled(kernel_id, 1); }
-
-extern "C" int rpo_profile_stop(int64_t* n_launches, double* total_ms, double* total_flops, double* total_bytes) {
+extern "C" int rpo_profile_stop(int kernel_id, int64_t* n_launches, double* total_ms, double* total_flops,
+                                double* total_bytes) {
+    if (kernel_id <= 0 || kernel_id >= kKidCount) return fail(RPO_EINVAL, "rpo_profile_stop: unknown kernel id");
     if (!n_launches || !total_ms || !total_flops || !total_bytes)
         return fail(RPO_EINVAL, "rpo_profile_stop: NULL argument");
+    Profile& p = g_prof[kernel_id];
     double ms = 0.0;
-    const size_t n = g_prof.used / 2;
-    if (n) HIP_TRY(hipEventSynchronize(g_prof.events[g_prof.used - 1]));
+    const size_t n = p.used / 2;
+    if (n) HIP_TRY(hipEventSynchronize(p.events[p.used - 1]));
     for (size_t i = 0; i < n; ++i) {
         float t = 0.f;
-        HIP_TRY(hipEventElapsedTime(&t, g_prof.events[2 * i], g_prof.events[2 * i + 1]));
+        HIP_TRY(hipEventElapsedTime(&t, p.events[2 * i], p.events[2 * i + 1]));
         ms += t;
     }
     *n_launches = (int64_t)n;
     *total_ms = ms;
-    *total_flops = g_prof.flops;
-    *total_bytes = g_prof.bytes;
-    g_prof.kernel_id = 0;
-    g_prof.used = 0;
+    *total_flops = p.flops;
+    *total_bytes = p.bytes;
+    p.on = false;
+    p.used = 0;
     return RPO_OK;
 }
 

@@ -1,19 +1,25 @@
-"""Parity at the benchmark's full size: the whole C1 workload (1.5B-shaped decoder, 28
-layers, 64 groups x 8 rollouts, ~2000-token shared prefixes) runs on the GPU in the launch
-configuration bench.py times; the oracle then recomputes sampled outputs one by one --
-the last-prefix logits row of one group, the first decode steps of two of its rollouts,
-their suffix log-probs -- plus everything that is cheap at any size (sampler consistency
-on those rows, advantages of every group, token accounting).
+"""Parity at the benchmark's full size.
 
-Tolerance.  A bf16 model stores activations and KV in bf16.  Through 28 random-init
-layers that storage rounding alone moves the logits by ~1.5e-2 rms / several 1e-2 max
-(any bf16-operand implementation, on any hardware): an absolute 2e-2 bound on the maximum
-is not a property of a correct implementation at this depth.  The test therefore measures
-the quantisation noise floor with the oracle itself -- the distance between the exact
-fp64 forward and the fp64 forward that rounds the stored tensors to bf16 -- and requires
-the GPU to stay within a small factor of it (rms <= 1.6 x floor, max <= 2.5 x floor max).
-A wrong kernel (a dropped page, a wrong head mapping, a stale KV row) moves logits by
-O(1) x their standard deviation, one to two orders of magnitude above the floor.
+C1: the whole workload (1.5B-shaped decoder, 28 layers, 64 groups x 8 rollouts, ~2000-token
+shared prefixes) runs on the GPU in the launch configuration bench.py times; the oracle then
+recomputes sampled outputs one by one -- the last-prefix logits row of one group, the first
+decode steps of two of its rollouts, their suffix log-probs -- plus everything that is cheap at
+any size (sampler consistency on those rows, advantages of every group, token accounting).
+
+7B shape: all 28 layers at the 7B widths with the benchmark's 256 rollout rows (32 groups x 8), so
+every decode kernel takes the tile shapes it takes in the 7B benchmark; the prefixes are cut to
+~500 tokens (256-token prompt + 256-token cached answer, 8-12 regenerated) so that the fp64
+oracle can afford one group's prefill: 7 shared pages plus a partial one instead of 63.
+
+Tolerance.  bf16 matrix operands and a bf16 KV cache: through 28 random-init layers that
+quantisation alone moves the logits by ~1.5e-2 rms / several 1e-2 max (any bf16-operand
+implementation, on any hardware): an absolute 2e-2 bound on the maximum is not a property of a
+correct implementation at this depth.  The tests therefore measure the quantisation floor with
+the oracle itself -- the distance between the exact fp64 forward and the fp64 forward that
+rounds the minimal set of tensors such a model must round -- and require the GPU to stay within
+FLOOR_RMS x its rms and FLOOR_MAX x its maximum.  A wrong kernel (a dropped page, a wrong head
+mapping, a stale KV row) moves logits by O(1) x their standard deviation, one to two orders of
+magnitude above the floor.
 """
 import time
 
@@ -31,6 +37,7 @@ pytestmark = pytest.mark.gpu
 
 N_STEPS = 3          # decode steps checked per rollout (plus the prefill row)
 ROLLOUTS = (0, 5)    # rollouts of the checked group
+FLOOR_RMS, FLOOR_MAX = 1.25, 1.5
 
 
 def _f64_weights(w):
@@ -39,13 +46,11 @@ def _f64_weights(w):
                 layers=[{k: cv(v) for k, v in lw.items()} for lw in w["layers"]])
 
 
-@pytest.mark.timeout(1500)
-def test_c1_full_size_sampled_outputs():
+def _slice_parity(cfg, n_steps, max_rows, check_fraction=True):
     from paper_2601_19404_amd import binding as rpo
     from paper_2601_19404_amd import rollout
     rpo.lib()
     rpo.rpo_set_kernel_path(0)
-    cfg = synth.C1
     mc = cfg.model
     w = synth.make_weights(mc, seed=1234, device="cuda")
     model = rpo.rpo_model_create(mc, w)
@@ -57,22 +62,23 @@ def test_c1_full_size_sampled_outputs():
     rewards = wl.rewards[order]
     ng, G = cfg.n_groups, cfg.G
     max_prefix = cfg.prompt_len + cfg.traj_len - int(m.min())
-    batch = rpo.rpo_batch_create(model, ng, G, max_prefix, int(m.max()), 64, 16384)
+    batch = rpo.rpo_batch_create(model, ng, G, max_prefix, int(m.max()), 64, max_rows)
     seq_ids = util.seq_ids_dev(ng * G)
     t0 = time.perf_counter()
     res = rollout.suffix_rollout(batch, prompts, cached, m, cfg.temperature, 3, seq_ids,
-                                 keep_logits=N_STEPS + 1)
+                                 keep_logits=n_steps + 1)
     packed, cu_s = rollout.pack_suffixes(res.tokens, m, G)
     lp_out = torch.empty(int(cu_s[-1]), dtype=torch.float32, device="cuda")
     rpo.rpo_suffix_logprobs(batch, packed, cu_s, cfg.temperature, lp_out)
     adv = torch.empty(ng, G, dtype=torch.float32, device="cuda")
     rpo.grpo_advantages(torch.from_numpy(rewards).cuda(), ng, G, 0, 0.0, adv)
     torch.cuda.synchronize()
-    print(f"GPU: full C1 rollout + log-probs in {time.perf_counter() - t0:.2f} s", flush=True)
+    print(f"GPU: {cfg.name} rollout + log-probs in {time.perf_counter() - t0:.2f} s", flush=True)
 
     # cheap at any size
     assert res.n_generated == int(m.sum()) * G
-    assert 0.05 <= m.mean() / cfg.traj_len <= 0.10          # ~7.5 % of the tokens are regenerated
+    if check_fraction:
+        assert 0.05 <= m.mean() / cfg.traj_len <= 0.10      # ~7.5 % of the tokens are regenerated
     np.testing.assert_array_equal(adv.cpu().numpy(), oadv.grpo_advantages(rewards))
     toks = res.tokens.cpu().numpy()
     slp = res.sample_logprobs.cpu().numpy()
@@ -90,8 +96,9 @@ def test_c1_full_size_sampled_outputs():
     toks1 = toks[g * G:(g + 1) * G]
     slp1 = slp[g * G:(g + 1) * G]
 
-    # oracle, exact and with bf16 storage, on the sampled rows
+    # oracle, exact and with bf16 operands / cache, on the sampled rows
     w64 = _f64_weights(w)
+    del w
     prefix = np.concatenate([prompts[g], cached[g][:cfg.traj_len - int(m[g])]])
     sid = np.arange(g * G, (g + 1) * G).astype(np.uint64)
     stats = {}
@@ -103,7 +110,7 @@ def test_c1_full_size_sampled_outputs():
         rows = {"prefill": z0}
         for ri in ROLLOUTS:
             kv = kv0.copy()
-            for j in range(1, N_STEPS + 1):
+            for j in range(1, n_steps + 1):
                 rows[(ri, j)] = T.decode_step(shape, w64, int(toks1[ri, j - 1]), kv)
         stats[storage] = rows
         print(f"oracle ({storage}) pass: {time.perf_counter() - t0:.1f} s", flush=True)
@@ -117,23 +124,35 @@ def test_c1_full_size_sampled_outputs():
     floor_rms, floor_max = np.sqrt(np.mean(floor ** 2)), np.abs(floor).max()
     err_rms, err_max = np.sqrt(np.mean(err ** 2)), np.abs(err).max()
     sd = np.concatenate([exact[k] for k in exact]).std()
-    print(f"logits std {sd:.3f}; bf16 storage floor: rms {floor_rms:.3e} max {floor_max:.3e}; "
-          f"GPU vs exact fp64: rms {err_rms:.3e} max {err_max:.3e}", flush=True)
-    assert err_rms <= 1.6 * floor_rms and err_max <= 2.5 * floor_max
+    print(f"logits std {sd:.3f}; bf16 floor: rms {floor_rms:.3e} max {floor_max:.3e}; "
+          f"GPU vs exact fp64: rms {err_rms:.3e} max {err_max:.3e} (x{err_rms / floor_rms:.2f}, "
+          f"x{err_max / floor_max:.2f})", flush=True)
+    assert err_rms <= FLOOR_RMS * floor_rms and err_max <= FLOOR_MAX * floor_max
     assert err_rms < 0.05 * sd
 
     # integer contract on the GPU's own logits rows
     t, _ = osampler.sample(kept[0], cfg.temperature, 3, sid, 0, row_map=np.zeros(G, np.int64))
     np.testing.assert_array_equal(t, toks1[:, 0])
-    for j in range(1, N_STEPS + 1):
+    for j in range(1, n_steps + 1):
         t, _ = osampler.sample(kept[j], cfg.temperature, 3, sid, j)
         np.testing.assert_array_equal(t, toks1[:, j])
 
     # suffix log-probs of the checked tokens (from the full-size log-prob pass when the tokens agree)
     for ri in ROLLOUTS:
         r = g * G + ri
-        for j in range(N_STEPS + 1):
+        for j in range(n_steps + 1):
             z = exact["prefill"] if j == 0 else exact[(ri, j)]
             ref = T.log_softmax(z / cfg.temperature)[toks1[ri, j]]
-            assert abs(slp1[ri, j] - ref) <= 2.5 * floor_max + 1e-3
-            assert abs(lp_gpu[cu_s[r] + j] - ref) <= 2.5 * floor_max + 1e-3
+            assert abs(slp1[ri, j] - ref) <= FLOOR_MAX * floor_max + 1e-3
+            assert abs(lp_gpu[cu_s[r] + j] - ref) <= FLOOR_MAX * floor_max + 1e-3
+
+
+@pytest.mark.timeout(1500)
+def test_c1_full_size_sampled_outputs():
+    _slice_parity(synth.C1, N_STEPS, 16384)
+
+
+@pytest.mark.timeout(1500)
+def test_7b_shape_28_layers_256_rows_sampled_outputs():
+    cfg = synth.WorkloadCfg("C3-7B-short-prefix", synth.QWEN_7B, 32, 8, 256, 256, 8, 12)
+    _slice_parity(cfg, 2, 16384, check_fraction=False)

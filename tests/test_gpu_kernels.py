@@ -270,9 +270,18 @@ def test_profile_sampling_and_peak_probe(rpo):
         rpo.rpo_profile_start(rpo.KERNEL_IDS["gemm256"], every)
         for _ in range(10):
             rpo.rpo_gemm_nt(a, w, c, 1, None)
-        n, ms, flops, nbytes = rpo.rpo_profile_stop()
+        n, ms, flops, nbytes = rpo.rpo_profile_stop(rpo.KERNEL_IDS["gemm256"])
         assert n == expect and ms > 0.0
         assert flops == pytest.approx(expect * 2.0 * 300 * 520 * 1536)
+    # two kernels timed at once: the SwiGLU instantiation of the same tile has an id of its own
+    act = torch.zeros(300, 256, device="cuda", dtype=torch.bfloat16)
+    rpo.rpo_profile_start(rpo.KERNEL_IDS["gemm256"], 1)
+    rpo.rpo_profile_start(rpo.KERNEL_IDS["gemm256_swiglu"], 1)
+    rpo.rpo_gemm_nt(a, w, c, 1, None)
+    rpo.rpo_gemm_nt(a, w[:512], act, 3, None)
+    rpo.rpo_gemm_nt(a, w[:512], act, 3, None)
+    assert rpo.rpo_profile_stop(rpo.KERNEL_IDS["gemm256"])[0] == 1
+    assert rpo.rpo_profile_stop(rpo.KERNEL_IDS["gemm256_swiglu"])[0] == 2
     rpo.rpo_set_kernel_path(0)
     with pytest.raises(rpo.RpoError):
         rpo.rpo_profile_start(rpo.KERNEL_IDS["gemm256"], 0)
