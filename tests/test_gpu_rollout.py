@@ -34,7 +34,7 @@ pytestmark = pytest.mark.gpu
 
 TOL = {"f32": 1e-4, "bf16": 2e-2}
 FLOOR_RMS, FLOOR_MAX = 1.25, 1.5     # allowed GPU error in units of the bf16 quantisation floor
-ULP_RMS, ULP_MAX = 1.0, 4.0          # allowed distance to the rounded forward, in bf16 ulps of the logit scale
+ULP_RMS, ULP_MAX = 1.25, 6.0         # allowed distance to the rounded forward, in bf16 ulps of the logit scale
 
 
 def bf16_ulp(x: float) -> float:
