@@ -32,6 +32,19 @@ int rpo_gemm_nt(const void *a_dev, int64_t lda, const void *w_dev, int64_t ldw, 
                 int32_t M, int32_t N, int32_t K, int32_t dtype, int32_t epilogue, void *ws_dev,
                 size_t ws_bytes, void *stream);
 
+/* rpo_gemm_nt for callers that cannot allocate or pass a workspace (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): the same contraction, kernels and
+ * results, with the K-split partial sums in a fixed 16 MiB device array that belongs to the
+ * library (one copy per GPU, held until the process ends).  Allocates nothing, on the host or the
+ * device.  Arguments as rpo_gemm_nt.  A problem whose K split needs more than 16 MiB of partial
+ * sums (splits * M * N * 4 bytes; only skinny problems with a deep K are split) is rejected with
+ * RPO_ENOMEM and nothing is enqueued.  All calls on one GPU share the array: calls that may run
+ * concurrently on one GPU (different streams, different threads) race on it; calls on one
+ * stream are safe.  Nothing in the array needs clearing between calls (every partial sum is
+ * written before it is read).  Errors: RPO_EINVAL, RPO_ENOMEM, RPO_EHIP. */
+int rpo_gemm_nt_noalloc(const void *a_dev, int64_t lda, const void *w_dev, int64_t ldw, void *c_dev, int64_t ldc,
+                        int32_t M, int32_t N, int32_t K, int32_t dtype, int32_t epilogue, void *stream);
+
 /* Practical ceilings of the GPU the library runs on, for roofline reports: the rate of a plain
  * device-to-device copy of `bytes` bytes (read + write counted, GB/s, best of three launches) and
  * of a back-to-back bf16 32x32x16 MFMA issue loop with changing operands (TFLOP/s, two workgroups

@@ -73,6 +73,7 @@ def lib() -> C.CDLL:
     L.rpo_objective_forward.argtypes = [vp, vp, vp, vp, vp, i32, i32, f32, f32, vp, vp, vp, vp]
     L.rpo_shape_rewards.argtypes = [vp, vp, i32, i32, f32, f32, f32, vp, vp]
     L.rpo_gemm_nt.argtypes = [vp, i64, vp, i64, vp, i64, i32, i32, i32, i32, i32, vp, sz, vp]
+    L.rpo_gemm_nt_noalloc.argtypes = [vp, i64, vp, i64, vp, i64, i32, i32, i32, i32, i32, vp]
     L.rpo_probe_peaks.argtypes = [vp, vp, sz, vp, C.POINTER(C.c_double), C.POINTER(C.c_double), vp]
     L.rpo_set_kernel_path.argtypes = [C.c_int]
     L.rpo_profile_start.argtypes = [C.c_int, C.c_int]
@@ -80,7 +81,8 @@ def lib() -> C.CDLL:
                                    C.POINTER(C.c_double)]
     for name in ("rpo_model_create", "rpo_batch_create", "rpo_prefill_prefix", "rpo_kv_fork",
                  "rpo_decode_step", "rpo_sample", "rpo_suffix_logprobs", "grpo_advantages",
-                 "rpo_shape_rewards", "rpo_objective_forward", "rpo_gemm_nt", "rpo_set_kernel_path", "rpo_profile_start", "rpo_profile_stop", "rpo_probe_peaks"):
+                 "rpo_shape_rewards", "rpo_objective_forward", "rpo_gemm_nt", "rpo_gemm_nt_noalloc", "rpo_set_kernel_path",
+                 "rpo_profile_start", "rpo_profile_stop", "rpo_probe_peaks"):
         getattr(L, name).restype = C.c_int
     _lib = L
     return L
@@ -89,7 +91,7 @@ def lib() -> C.CDLL:
 EXPORTS = ("rpo_model_create", "rpo_model_destroy", "rpo_kv_pool_bytes", "rpo_workspace_bytes",
            "rpo_batch_create", "rpo_batch_destroy", "rpo_prefill_prefix", "rpo_kv_fork",
            "rpo_decode_step", "rpo_sample", "rpo_suffix_logprobs", "grpo_advantages",
-           "rpo_shape_rewards", "rpo_objective_forward", "rpo_last_error", "rpo_gemm_nt", "rpo_set_kernel_path", "rpo_profile_start",
+           "rpo_shape_rewards", "rpo_objective_forward", "rpo_last_error", "rpo_gemm_nt", "rpo_gemm_nt_noalloc", "rpo_set_kernel_path", "rpo_profile_start",
            "rpo_profile_stop", "rpo_probe_peaks")
 
 
@@ -311,6 +313,21 @@ def rpo_gemm_nt(a_dev: torch.Tensor, w_dev: torch.Tensor, c_dev: torch.Tensor, e
     _check(lib().rpo_gemm_nt(a_dev.data_ptr(), a_dev.stride(0), w_dev.data_ptr(), w_dev.stride(0),
                              c_dev.data_ptr(), c_dev.stride(0), M, N, K, dt, epilogue, _ptr(ws_dev),
                              0 if ws_dev is None else ws_dev.numel(), _stream(stream)))
+
+
+def rpo_gemm_nt_noalloc(a_dev: torch.Tensor, w_dev: torch.Tensor, c_dev: torch.Tensor, epilogue: int,
+                        stream=None) -> None:
+    """rpo_gemm_nt with the library's own fixed scratch for K-split partial sums (no workspace
+    argument, nothing allocated)."""
+    M, K = a_dev.shape
+    N, K2 = w_dev.shape
+    n_out = N // 2 if epilogue == 3 else N
+    if K != K2 or tuple(c_dev.shape) != (M, n_out) or a_dev.stride(1) != 1 or w_dev.stride(1) != 1 \
+            or c_dev.stride(1) != 1:
+        raise ValueError("shape / stride mismatch")
+    dt = RPO_F32 if a_dev.dtype == torch.float32 else RPO_BF16
+    _check(lib().rpo_gemm_nt_noalloc(a_dev.data_ptr(), a_dev.stride(0), w_dev.data_ptr(), w_dev.stride(0),
+                                     c_dev.data_ptr(), c_dev.stride(0), M, N, K, dt, epilogue, _stream(stream)))
 
 
 def rpo_set_kernel_path(path: int) -> None:

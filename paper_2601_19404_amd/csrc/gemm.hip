@@ -1223,6 +1223,15 @@ int gemm_fuses_max(const GemmArgs& a) {
     return ceil_div(a.N, 256) * 4;
 }
 
+size_t gemm_splitk_scratch_bytes(const GemmArgs& a) {
+    if (!mfma_ok(a) || a.M <= 0 || a.N <= 0) return 0;
+    GemmArgs u = a;
+    u.ws = (void*)(uintptr_t)256;  // never dereferenced: only "a workspace exists"
+    u.ws_bytes = ~(size_t)0;
+    const int splits = pick_splits(u, pick_tile(u));
+    return splits > 1 ? (size_t)splits * a.M * a.N * sizeof(float) : 0;
+}
+
 int gemm_kernel_id(const GemmArgs& a) {
     if (!mfma_ok(a)) return kKidGemmGeneric;
     const int id = pick_tile(a).id;

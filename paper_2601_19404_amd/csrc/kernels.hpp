@@ -103,6 +103,9 @@ enum KernelId : int {
 };
 // Which kernel launch_gemm picks for these arguments.
 int gemm_kernel_id(const GemmArgs& a);
+// Bytes of fp32 K-split partial sums launch_gemm would write for these arguments if the
+// workspace were unlimited (0 = the problem is not split along K); a.ws / a.ws_bytes are ignored.
+size_t gemm_splitk_scratch_bytes(const GemmArgs& a);
 
 // ---- elementwise ---------------------------------------------------------------
 // x[r, :] = embed[tokens[idx(r)], :] as fp32, idx(r) = tok_index ? tok_index[r] : r;

@@ -980,3 +980,60 @@ extern "C" int rpo_gemm_nt(const void* a_dev, int64_t lda, const void* w_dev, in
                   (hipStream_t)stream, [&] { return launch_gemm(g, (hipStream_t)stream); }));
     return RPO_OK;
 }
+
+// ---------------------------------------------------------------------------
+// rpo_gemm_nt without a workspace argument and without any allocation: the K-split partial
+// sums go to a fixed device array that is part of the library's code object.
+// ---------------------------------------------------------------------------
+namespace {
+constexpr size_t kScratchBytes = (size_t)16 << 20;
+constexpr int kMaxDevices = 64;
+}  // namespace
+// One copy per GPU the library is loaded on, held until the process ends.  In host code this
+// name is only a handle for hipGetSymbolAddress: kernels and copies take the looked-up pointer.
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+namespace {
+void* g_scratch_ptr[kMaxDevices] = {};  // device address of `scratch` on each device, looked up once
+}
+
+extern "C" int rpo_gemm_nt_noalloc(const void* a_dev, int64_t lda, const void* w_dev, int64_t ldw, void* c_dev,
+                                   int64_t ldc, int32_t M, int32_t N, int32_t K, int32_t dtype, int32_t epilogue,
+                                   void* stream) {
+    if (!a_dev || !w_dev || !c_dev) return fail(RPO_EINVAL, "rpo_gemm_nt_noalloc: NULL argument");
+    if (M < 0 || N < 0 || K < 1 || lda < K || ldw < K || ldc < (epilogue == 3 ? N / 2 : N))
+        return fail(RPO_EINVAL, "rpo_gemm_nt_noalloc: bad sizes");
+    if (dtype != RPO_F32 && dtype != RPO_BF16) return fail(RPO_EINVAL, "rpo_gemm_nt_noalloc: unknown dtype");
+    if (epilogue < 0 || epilogue > 3) return fail(RPO_EINVAL, "rpo_gemm_nt_noalloc: unknown epilogue");
+    if (epilogue == 3 && (N % 2)) return fail(RPO_EINVAL, "rpo_gemm_nt_noalloc: SwiGLU needs N = 2F");
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(RPO_EINVAL, "rpo_gemm_nt_noalloc: device index %d not supported", dev);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(RPO_EHIP, "rpo_gemm_nt_noalloc: the scratch array has no device address");
+        g_scratch_ptr[dev] = p;
+    }
+    GemmArgs g;
+    g.A = a_dev;
+    g.lda = lda;
+    g.W = w_dev;
+    g.ldw = ldw;
+    g.C = c_dev;
+    g.ldc = ldc;
+    g.M = M;
+    g.N = N;
+    g.K = K;
+    g.dtype = dtype;
+    g.epilogue = epilogue;
+    g.path = g_kernel_path;
+    g.ws = g_scratch_ptr[dev];
+    g.ws_bytes = kScratchBytes;
+    const size_t need = gemm_splitk_scratch_bytes(g);
+    if (need > kScratchBytes)
+        return fail(RPO_ENOMEM,
+                    "rpo_gemm_nt_noalloc: this problem splits K and needs %zu bytes of partial sums; the static "
+                    "scratch holds %zu (use rpo_gemm_nt with a workspace)", need, kScratchBytes);
+    HIP_TRY(launch_gemm(g, (hipStream_t)stream));
+    return RPO_OK;
+}
