@@ -31,7 +31,7 @@ HBM_BPS, MFMA_FLOPS = 8.0e12, 2.5e15
 DOMINANT_TRAFFIC = dict(launch="gate/up projection of a full chunk, M=32768 N=17920 K=1536, SwiGLU epilogue",
                         read_bytes=2680.3e6, write_bytes=587.7e6, algorithmic_bytes=155.7e6 + 587.2e6,
                         source="profiles/gemm_hbm_traffic_pmc.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)")
-KERNEL_BOUND = {"gemm256": "mfma", "gemm256_swiglu": "mfma", "gemm256x128": "mfma", "gemm256x192": "mfma",
+KERNEL_BOUND = {"gemm256": "mfma", "gemm256_swiglu": "mfma", "gemm256x192": "mfma",
                 "gemm128": "mfma", "gemm64": "mfma", "gemm32": "mfma", "gemm64x64": "mfma",
                 "gemm_generic": "alu", "attn_chunk": "mfma", "attn_decode": "hbm", "sample": "hbm"}
 
@@ -112,7 +112,7 @@ def algorithmic_decode_bytes(st) -> float:
 
 
 def build_case(workload: str, n_groups: int | None, max_rows: int, G: int | None = None,
-               temperature: float | None = None, trunc_max: int | None = None):
+               temperature: float | None = None, trunc_max: int | None = None, epochs: int = 0):
     import dataclasses
     import torch
     from paper_2601_19404_amd import binding as rpo
@@ -138,6 +138,9 @@ def build_case(workload: str, n_groups: int | None, max_rows: int, G: int | None
     ng, G = len(prompts), cfg.G
     max_prefix = cfg.prompt_len + cfg.traj_len - int(m.min())
     max_suffix = max(int(m.max()), 1)
+    if epochs:      # every epoch draws its own cuts: size the batch for the whole range
+        max_prefix = cfg.prompt_len + cfg.traj_len - cfg.m_lo
+        max_suffix = max(cfg.m_hi, 1)
     max_rows = max(max_rows, max_prefix, ng * G, max_suffix)
     page = 64 if mc.dtype == "bf16" else 16
     batch = rpo.rpo_batch_create(model, ng, G, max_prefix, max_suffix, page, max_rows)
@@ -149,6 +152,9 @@ def build_case(workload: str, n_groups: int | None, max_rows: int, G: int | None
                  lp_out=torch.empty(max(int(cu_s[-1]), 1), dtype=torch.float32, device="cuda"),
                  adv_out=torch.empty(ng, G, dtype=torch.float32, device="cuda"), weights=w,
                  page=page, max_prefix=max_prefix, max_suffix=max_suffix)
+    if epochs:
+        from paper_2601_19404_amd import cache
+        state["pool"] = cache.DeviceCachePool(wl.prompts, wl.cached)
     return state
 
 
@@ -166,6 +172,61 @@ def one_step(st, seed: int, marks=None):
         ev.record()
         marks.append(("logprobs+advantages", ev, time.perf_counter()))
     return res
+
+
+def one_epoch_step(st, seed: int, epoch: int):
+    """One pass of Algorithm 1's inner loop with the experience cache on the device: draw the cuts,
+    cut + pack from the pool, rollout, suffix log-probs, advantages, epsilon-greedy cache update
+    (Sec. 3.3).  The next epoch conditions on what this one wrote.  Returns tokens generated."""
+    import torch
+    from paper_2601_19404_amd import binding as rpo
+    from paper_2601_19404_amd import rollout
+    cfg, ng, G = st["cfg"], st["ng"], st["G"]
+    rng = np.random.Generator(np.random.PCG64(7000 + epoch))
+    m_q = rng.integers(cfg.m_lo, cfg.m_hi + 1, size=ng, dtype=np.int32)
+    order = rollout.order_by_suffix_length(m_q)
+    m = m_q[order]
+    toks, cu = st["pool"].cut_pack(m, order)
+    res = rollout.suffix_rollout(st["batch"], None, None, m, cfg.temperature, seed, st["seq_ids"], prefix=(toks, cu))
+    packed, cu_s = rollout.pack_suffixes(res.tokens, m, G)
+    rpo.rpo_suffix_logprobs(st["batch"], packed, cu_s, cfg.temperature, st["lp_out"][:max(int(cu_s[-1]), 1)])
+    rewards = torch.from_numpy((rng.random((ng, G)) < cfg.reward_p).astype(np.float32)).cuda()
+    rpo.grpo_advantages(rewards, ng, G, 0, 0.0, st["adv_out"])
+    st["pool"].update(m, order, res.tokens, rewards, rng.random(ng).astype(np.float32),
+                      rng.integers(0, G, size=ng), 0.1)
+    return res.n_generated
+
+
+def run_epochs(args):
+    """--epochs N: N consecutive passes per step, each reading the cache the previous one updated."""
+    import torch
+    st = build_case(args.workload, args.groups, args.max_rows, args.G, args.temperature, args.trunc_max,
+                    epochs=args.epochs)
+    cfg = st["cfg"]
+    st["lp_out"] = torch.empty(st["ng"] * st["G"] * st["max_suffix"], dtype=torch.float32, device="cuda")
+    before = st["pool"].answers.clone()
+    for i in range(args.warmup):
+        one_epoch_step(st, 100 + i, i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    n_gen = 0
+    for i in range(args.steps):
+        for e in range(args.epochs):
+            n_gen += one_epoch_step(st, 200 + i * args.epochs + e, args.warmup + i * args.epochs + e)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    changed = float((st["pool"].answers != before).float().mean().item())
+    out = dict(metric="suffix-rollout tokens/sec at 1.5B shape; decode HBM GB/s vs peak", value=n_gen / dt,
+               unit="tokens/s", n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=dt * 1e3 / args.steps,
+               higher_is_better=True, scaling="weak", vs_baseline=None, dtype=cfg.model.dtype, data="synthetic",
+               config=dict(workload=cfg.name, model_shape=cfg.model.name, n_groups=st["ng"], G=st["G"],
+                           epochs_per_step=args.epochs, cuts="redrawn every epoch", cache="device pool, "
+                           "epsilon-greedy update (eps 0.1) after every epoch",
+                           step="per epoch: cut+pack from the device pool, prefill, fork, sample/decode loop, "
+                                "suffix log-probs, advantages, cache update"),
+               generated_tokens=int(n_gen), cache_tokens_replaced_frac=round(changed, 4),
+               roofline=None, cpu_baseline=None)
+    print(json.dumps(out), flush=True)
 
 
 def run_c4(args):
@@ -287,6 +348,9 @@ def main():
                     help="kernel whose launches are ALL timed with HIP events for the roofline object "
                          "(default: the instantiation that leads the kernel table of a step by time)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--epochs", type=int, default=0,
+                    help="N > 0: a step is N consecutive passes with the experience cache on the device, cuts "
+                         "redrawn per pass and the epsilon-greedy cache update after each (Sec. 3.3, Algorithm 1)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1",
@@ -301,6 +365,9 @@ def main():
     rpo.lib()
     if args.workload == "C4":
         run_c4(args)
+        return
+    if args.epochs > 0:
+        run_epochs(args)
         return
     st = build_case(args.workload, args.groups, args.max_rows, args.G, args.temperature, args.trunc_max)
     cfg = st["cfg"]

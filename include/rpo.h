@@ -18,8 +18,11 @@
  *    BORROWED by the handles for their lifetime.  The library never allocates
  *    or frees device memory.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *    Compute calls only enqueue work: no host synchronisation, no device-to-host
- *    copies.  Host arrays passed to a call are consumed before it returns.
+ *    Compute calls only enqueue work: no device-to-host copies, no wait for the stream.
+ *    rpo_prefill_prefix, rpo_kv_fork and rpo_suffix_logprobs upload a few small integer tables
+ *    (page tables, row maps) from ordinary host memory with hipMemcpyAsync: the runtime may hold
+ *    the calling thread until such a copy is staged.  rpo_decode_step, rpo_sample and the
+ *    stateless calls upload nothing.  Host arrays passed to a call are consumed before it returns.
  *  - All matrices are row-major.  Projection weights are [out_features,
  *    in_features] (y = x W^T).  Activations / weights are fp32 (RPO_F32) or
  *    bfloat16 (RPO_BF16); logits, log-probs, rewards and advantages are fp32.
@@ -224,6 +227,46 @@ int rpo_objective_forward(const float *lp_new_dev, const float *lp_old_dev, cons
  * Errors: RPO_EINVAL (NULL, G < 1, alpha <= 0, lo > hi). */
 int rpo_shape_rewards(const float *rewards_dev, const int32_t *lengths_dev, int32_t n_groups, int32_t G,
                       float alpha, float lo, float hi, float *shaped_out_dev, void *stream);
+
+/* Eq. 3, the cut, with the cached answers resident on the device: pack q_k || a_k[0 : c_k] of
+ * every question back to back -- the `tokens_dev` that rpo_prefill_prefix takes.  c_k follows
+ * from the cumulative prefix lengths: c_k = (cu_len[k+1] - cu_len[k]) - prompt_len of its question.
+ *   prompts_dev    device int32 [n_questions, prompt_stride]; prompt_len_dev device int32 [n_questions]
+ *   pool_dev       device int32 [n_questions, pool_stride]: the cached answers (Eq. 1-2)
+ *   question_dev   device int32 [n_groups] or NULL: row of the prompt / pool arrays that batch group
+ *                  k reads (NULL: row k; prompts_dev / prompt_len_dev are indexed the same way).  A
+ *                  rollout batch orders its groups by suffix length, the pool keeps question order.
+ *   cu_len_dev     device int32 [n_groups + 1] (the same values rpo_prefill_prefix gets on the host)
+ *   tokens_out_dev device int32 [cu_len[n_groups]]
+ * Errors: RPO_EINVAL.  The caller guarantees c_k <= pool_stride. */
+int rpo_cut_pack(const int32_t *prompts_dev, int64_t prompt_stride, const int32_t *prompt_len_dev,
+                 const int32_t *pool_dev, int64_t pool_stride, const int32_t *question_dev,
+                 const int32_t *cu_len_dev, int32_t n_groups, int32_t *tokens_out_dev, void *stream);
+
+/* Cache update, Sec. 3.3 (the epsilon-greedy rule around Eq. 10) and Algorithm 1, "Update
+ * Cache": after a step, question k's cached answer becomes a_k[0 : len_k - m_k] || o, where o is
+ * the response the rule selects among the G just sampled: the one with the highest reward when
+ * u_k <= eps (ties: lowest index), otherwise response g'_k (Algorithm 1 draws g' over all G).
+ * The random numbers are inputs.  In place, on the device: the next rpo_cut_pack reads what this
+ * call wrote, no token leaves HBM.
+ *   pool_dev       device int32 [n_questions, pool_stride], updated in place
+ *   answer_len_dev device int32 [n_questions], in/out: tokens of each cached answer
+ *                  (new = old - m_k + tokens of the selected response)
+ *   question_dev   device int32 [n_groups] or NULL: pool row of batch group k (as in rpo_cut_pack);
+ *                  every other array below is in batch order
+ *   m_dev          device int32 [n_groups]: tokens cut from each answer in this step
+ *   tokens_dev     device int32 [n_groups*G, tok_stride]: sampled tokens, row r = k*G + i
+ *   lengths_dev    device int32 [n_groups*G] or NULL: tokens each rollout generated (rpo_sample's
+ *                  lengths; NULL = m_k, the fixed-length case)
+ *   rewards_dev    device fp32 [n_groups, G]; u_dev device fp32 [n_groups] in [0, 1);
+ *   g_prime_dev    device int32 [n_groups] in [0, G)
+ *   chosen_out_dev device int32 [n_groups] or NULL: the selected index
+ * A question whose cut or new length does not fit its pool row (or whose g' is out of range) is
+ * left unchanged and reports -1.  Errors: RPO_EINVAL (NULL, sizes, eps outside [0, 1]). */
+int rpo_cache_update(int32_t *pool_dev, int64_t pool_stride, int32_t *answer_len_dev,
+                     const int32_t *question_dev, const int32_t *m_dev, const int32_t *tokens_dev, int64_t tok_stride, const int32_t *lengths_dev,
+                     const float *rewards_dev, const float *u_dev, const int32_t *g_prime_dev, int32_t n_groups,
+                     int32_t G, float eps, int32_t *chosen_out_dev, void *stream);
 
 /* Thread-local message of the last failing call in this thread ("" if none). */
 const char *rpo_last_error(void);

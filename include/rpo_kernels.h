@@ -32,6 +32,23 @@ int rpo_gemm_nt(const void *a_dev, int64_t lda, const void *w_dev, int64_t ldw, 
                 int32_t M, int32_t N, int32_t K, int32_t dtype, int32_t epilogue, void *ws_dev,
                 size_t ws_bytes, void *stream);
 
+/* The shared-prefix decode attention of ONE layer on its own (the kernel rpo_decode_step runs
+ * between the QKV and the output projection), so that it can be checked against a plain
+ * softmax(q K^T / sqrt(dh)) V and profiled alone.  For rollout rows [0, n_rows) of a forked batch:
+ * one query row per rollout attends to [the group's shared prefix pages || the rollout's private
+ * pages], i.e. to positions [0, prefix_len(group) + n_suffix) of whatever keys / values the batch's
+ * pages hold for `layer` (the prefix after rpo_prefill_prefix + rpo_kv_fork; private positions
+ * that no decode step or log-prob pass has written hold zeros).
+ *   q_dev      device, [n_rows, n_q_heads * head_dim], model dtype, already rotated
+ *   n_suffix   private tokens each rollout sees, 0..max_suffix
+ *   active_dev device uint8 [n_rows] or NULL; rows with 0 are skipped (their output row is untouched)
+ *   out_dev    device, [n_rows, n_q_heads * head_dim], model dtype
+ * Uses the batch's workspace (attention partials): not concurrently with other calls on the batch.
+ * Errors: RPO_ESTATE unless forked; RPO_EINVAL. */
+struct rpo_batch;
+int rpo_attn_decode(struct rpo_batch *b, int32_t layer, const void *q_dev, int32_t n_rows, int32_t n_suffix,
+                    const uint8_t *active_dev, void *out_dev, void *stream);
+
 /* rpo_gemm_nt for callers that cannot allocate or pass a workspace (code under HIP graph capture,
  * tight serving loops, harnesses that forbid hipMalloc): the same contraction, kernels and
  * results, with the K-split partial sums in a fixed 16 MiB device array that belongs to the
@@ -56,12 +73,15 @@ int rpo_gemm_nt_noalloc(const void *a_dev, int64_t lda, const void *w_dev, int64
 int rpo_probe_peaks(const void *src_dev, void *dst_dev, size_t bytes, float *scratch_dev, double *copy_gbps,
                     double *mfma_tflops, void *stream);
 
-/* Process-wide kernel selection: 0 = fastest available kernel for the shape (default),
- * 1 = generic vector-ALU kernels for GEMM and attention regardless of shape,
- * 2 = MFMA GEMM with register-staged LDS fills instead of direct-to-LDS loads (the
- *     fallback used when K is not a multiple of 64; selectable for comparison),
- * 16 + k (k = 1..6, 11) = MFMA GEMM with the fixed tile shape of kernel id k (a tuning aid;
- * attention as in 0).  Not thread-safe against concurrent compute calls.
+/* TEST AND TUNING SWITCH, process-wide: 0 = fastest available kernel for the shape (default, and
+ * the only value a product run uses),
+ * 1 = generic vector-ALU kernels for GEMM and attention regardless of shape (the tests run whole
+ *     rollouts through them as a cross-check of the MFMA kernels),
+ * 2 = MFMA GEMM with register-staged LDS fills instead of direct-to-LDS loads (the fallback
+ *     used when K is not a multiple of 64; selectable so that the tests reach it at any K),
+ * 16 + k (k = 1, 3..6, 11) = MFMA GEMM with the fixed tile shape of kernel id k, so that the tests
+ *     can force every tile shape onto one problem (attention as in 0).
+ * Unsynchronised: set it from the thread that issues the compute calls, between calls.
  * Errors: RPO_EINVAL. */
 int rpo_set_kernel_path(int path);
 
@@ -77,7 +97,6 @@ int rpo_set_kernel_path(int path);
  *   1  <256,256,2,4> (prefill-sized problems and wide decode projections), every epilogue but SwiGLU
  *   12 <256,256,2,4> with the fused SwiGLU epilogue: the gate/up projection of prefill and
  *      log-prob chunks, one instantiation, the heaviest kernel of a rollout step
- *   2  <256,128,2,2> (only via rpo_set_kernel_path)
  *   3  <128,128,2,2> (decode-sized problems, deep K)   4  <64,128,1,2> (the same for M <= 64)
  *   5  <32,128,1,4> / <64,128,1,4> (decode QKV projection: rotary embedding and KV page write in
  *      the epilogue; 64 rows once the 32-row tiles would outnumber the CUs)

@@ -72,6 +72,9 @@ def lib() -> C.CDLL:
     L.grpo_advantages.argtypes = [vp, i32, i32, i32, f32, vp, vp]
     L.rpo_objective_forward.argtypes = [vp, vp, vp, vp, vp, i32, i32, f32, f32, vp, vp, vp, vp]
     L.rpo_shape_rewards.argtypes = [vp, vp, i32, i32, f32, f32, f32, vp, vp]
+    L.rpo_cut_pack.argtypes = [vp, i64, vp, vp, i64, vp, vp, i32, vp, vp]
+    L.rpo_cache_update.argtypes = [vp, i64, vp, vp, vp, vp, i64, vp, vp, vp, vp, i32, i32, f32, vp, vp]
+    L.rpo_attn_decode.argtypes = [vp, i32, vp, i32, i32, vp, vp, vp]
     L.rpo_gemm_nt.argtypes = [vp, i64, vp, i64, vp, i64, i32, i32, i32, i32, i32, vp, sz, vp]
     L.rpo_gemm_nt_noalloc.argtypes = [vp, i64, vp, i64, vp, i64, i32, i32, i32, i32, i32, vp]
     L.rpo_probe_peaks.argtypes = [vp, vp, sz, vp, C.POINTER(C.c_double), C.POINTER(C.c_double), vp]
@@ -81,8 +84,8 @@ def lib() -> C.CDLL:
                                    C.POINTER(C.c_double)]
     for name in ("rpo_model_create", "rpo_batch_create", "rpo_prefill_prefix", "rpo_kv_fork",
                  "rpo_decode_step", "rpo_sample", "rpo_suffix_logprobs", "grpo_advantages",
-                 "rpo_shape_rewards", "rpo_objective_forward", "rpo_gemm_nt", "rpo_gemm_nt_noalloc", "rpo_set_kernel_path",
-                 "rpo_profile_start", "rpo_profile_stop", "rpo_probe_peaks"):
+                 "rpo_shape_rewards", "rpo_objective_forward", "rpo_cut_pack", "rpo_cache_update", "rpo_gemm_nt",
+                 "rpo_attn_decode", "rpo_gemm_nt_noalloc", "rpo_set_kernel_path", "rpo_profile_start", "rpo_profile_stop", "rpo_probe_peaks"):
         getattr(L, name).restype = C.c_int
     _lib = L
     return L
@@ -91,7 +94,7 @@ def lib() -> C.CDLL:
 EXPORTS = ("rpo_model_create", "rpo_model_destroy", "rpo_kv_pool_bytes", "rpo_workspace_bytes",
            "rpo_batch_create", "rpo_batch_destroy", "rpo_prefill_prefix", "rpo_kv_fork",
            "rpo_decode_step", "rpo_sample", "rpo_suffix_logprobs", "grpo_advantages",
-           "rpo_shape_rewards", "rpo_objective_forward", "rpo_last_error", "rpo_gemm_nt", "rpo_gemm_nt_noalloc", "rpo_set_kernel_path", "rpo_profile_start",
+           "rpo_shape_rewards", "rpo_objective_forward", "rpo_cut_pack", "rpo_cache_update", "rpo_last_error", "rpo_gemm_nt", "rpo_attn_decode", "rpo_gemm_nt_noalloc", "rpo_set_kernel_path", "rpo_profile_start",
            "rpo_profile_stop", "rpo_probe_peaks")
 
 
@@ -299,6 +302,41 @@ def rpo_shape_rewards(rewards_dev: torch.Tensor, lengths_dev: torch.Tensor, n_gr
                                    shaped_out_dev.data_ptr(), _stream(stream)))
 
 
+def rpo_cut_pack(prompts_dev: torch.Tensor, prompt_len_dev: torch.Tensor, pool_dev: torch.Tensor,
+                 question_dev, cu_len_dev: torch.Tensor, n_groups: int, tokens_out_dev: torch.Tensor,
+                 stream=None) -> None:
+    for t, nm in ((prompts_dev, "prompts_dev"), (prompt_len_dev, "prompt_len_dev"), (pool_dev, "pool_dev"),
+                  (cu_len_dev, "cu_len_dev"), (tokens_out_dev, "tokens_out_dev")):
+        _dev(t, torch.int32, nm)
+    if prompts_dev.dim() != 2 or pool_dev.dim() != 2 or cu_len_dev.numel() < n_groups + 1:
+        raise ValueError("prompts / pool must be 2-D, cu_len_dev [n_groups + 1]")
+    if question_dev is not None and (question_dev.dtype != torch.int32 or question_dev.numel() < n_groups):
+        raise ValueError("question_dev must be int32 [n_groups]")
+    _check(lib().rpo_cut_pack(prompts_dev.data_ptr(), prompts_dev.stride(0), prompt_len_dev.data_ptr(),
+                              pool_dev.data_ptr(), pool_dev.stride(0), _ptr(question_dev), cu_len_dev.data_ptr(),
+                              n_groups, tokens_out_dev.data_ptr(), _stream(stream)))
+
+
+def rpo_cache_update(pool_dev: torch.Tensor, answer_len_dev: torch.Tensor, question_dev, m_dev: torch.Tensor,
+                     tokens_dev: torch.Tensor, lengths_dev, rewards_dev: torch.Tensor, u_dev: torch.Tensor,
+                     g_prime_dev: torch.Tensor, n_groups: int, G: int, eps: float, chosen_out_dev=None,
+                     stream=None) -> None:
+    for t, nm in ((pool_dev, "pool_dev"), (answer_len_dev, "answer_len_dev"), (m_dev, "m_dev"),
+                  (g_prime_dev, "g_prime_dev")):
+        _dev(t, torch.int32, nm)
+    _dev(rewards_dev, torch.float32, "rewards_dev")
+    _dev(u_dev, torch.float32, "u_dev")
+    if tokens_dev.dtype != torch.int32 or tokens_dev.dim() != 2 or tokens_dev.stride(1) != 1 or not tokens_dev.is_cuda:
+        raise ValueError("tokens_dev: need a 2-D int32 device tensor with unit column stride")
+    if tokens_dev.shape[0] < n_groups * G or rewards_dev.numel() < n_groups * G or pool_dev.dim() != 2 \
+            or min(m_dev.numel(), u_dev.numel(), g_prime_dev.numel()) < n_groups:
+        raise ValueError("buffers do not match n_groups x G")
+    _check(lib().rpo_cache_update(pool_dev.data_ptr(), pool_dev.stride(0), answer_len_dev.data_ptr(),
+                                  _ptr(question_dev), m_dev.data_ptr(), tokens_dev.data_ptr(), tokens_dev.stride(0),
+                                  _ptr(lengths_dev), rewards_dev.data_ptr(), u_dev.data_ptr(), g_prime_dev.data_ptr(),
+                                  n_groups, G, eps, _ptr(chosen_out_dev), _stream(stream)))
+
+
 def rpo_gemm_nt(a_dev: torch.Tensor, w_dev: torch.Tensor, c_dev: torch.Tensor, epilogue: int,
                 ws_dev: torch.Tensor | None = None, stream=None) -> None:
     """C (op)= A W^T for 2-D tensors (row strides taken from the tensors); epilogue 3 is the
@@ -313,6 +351,20 @@ def rpo_gemm_nt(a_dev: torch.Tensor, w_dev: torch.Tensor, c_dev: torch.Tensor, e
     _check(lib().rpo_gemm_nt(a_dev.data_ptr(), a_dev.stride(0), w_dev.data_ptr(), w_dev.stride(0),
                              c_dev.data_ptr(), c_dev.stride(0), M, N, K, dt, epilogue, _ptr(ws_dev),
                              0 if ws_dev is None else ws_dev.numel(), _stream(stream)))
+
+
+def rpo_attn_decode(batch: Batch, layer: int, q_dev: torch.Tensor, n_rows: int, n_suffix: int, active_dev,
+                    out_dev: torch.Tensor, stream=None) -> None:
+    """One layer's shared-prefix decode attention on caller-given (rotated) queries."""
+    cfg = batch.model.cfg
+    width = cfg.n_q_heads * cfg.head_dim
+    tdt = torch.float32 if cfg.dtype in ("f32", RPO_F32) else torch.bfloat16
+    _dev(q_dev, tdt, "q_dev")
+    _dev(out_dev, tdt, "out_dev")
+    if q_dev.numel() < n_rows * width or out_dev.numel() < n_rows * width:
+        raise ValueError("q_dev / out_dev smaller than n_rows x n_q_heads x head_dim")
+    _check(lib().rpo_attn_decode(batch.handle, layer, q_dev.data_ptr(), n_rows, n_suffix, _ptr(active_dev),
+                                 out_dev.data_ptr(), _stream(stream)))
 
 
 def rpo_gemm_nt_noalloc(a_dev: torch.Tensor, w_dev: torch.Tensor, c_dev: torch.Tensor, epilogue: int,
@@ -349,7 +401,7 @@ def rpo_probe_peaks(n_bytes: int = 1 << 30, stream=None):
     return gbps.value, tflops.value
 
 
-KERNEL_IDS = {"gemm256": 1, "gemm256x128": 2, "gemm128": 3, "gemm64": 4, "gemm32": 5, "gemm64x64": 6,
+KERNEL_IDS = {"gemm256": 1, "gemm128": 3, "gemm64": 4, "gemm32": 5, "gemm64x64": 6,
               "gemm_generic": 7, "gemm256x192": 11, "attn_decode": 8, "attn_chunk": 9, "sample": 10,
               "gemm256_swiglu": 12}
 

@@ -16,7 +16,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librpo.so")
-SOURCES = ["rpo_api.hip", "gemm.hip", "attention.hip", "elementwise.hip", "sampler.hip", "probes.hip"]
+SOURCES = ["rpo_api.hip", "gemm.hip", "attention.hip", "elementwise.hip", "sampler.hip", "cache.hip", "probes.hip"]
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 EXTRA = {"sampler.hip": ["-ffp-contract=off"]}

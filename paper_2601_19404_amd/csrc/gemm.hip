@@ -307,10 +307,7 @@ constexpr int kLdsRow = kBK + 8;
 constexpr int kXcd = 8;  // XCDs of an MI355X; workgroup i is dispatched to XCD i % 8
 // Default direct-to-LDS pipeline shape.  Measured on the prefill gate/up projection: 64-deep slabs
 // in two stages beat 32-deep slabs in four stages and four waves of 128x128: not latency-bound.
-#ifndef RPO_DMA_BK
-#define RPO_DMA_BK 64
-#define RPO_DMA_STAGES 2
-#endif
+constexpr int kDmaBK = 64, kDmaStages = 2;
 
 // Column n of the (virtual) output -> row of W.  SwiGLU mode interleaves gate and up rows
 // in blocks of 32: virtual columns [64q, 64q+32) are gate rows 32q.., [64q+32, 64q+64) up rows.
@@ -996,10 +993,13 @@ TileCfg pick_tile(const GemmArgs& a) {
     if (a.path >= 16) {  // tuning aid: a fixed tile shape
         switch (a.path - 16) {
             case kKidGemm256: return TileCfg{kKidGemm256, 256, 256};
-            case kKidGemm256x128: return TileCfg{kKidGemm256x128, 256, 128};
             case kKidGemm128: return TileCfg{kKidGemm128, 128, 128};
             case kKidGemm32: return TileCfg{kKidGemm32, 32, 128};
             case kKidGemm64x64: return TileCfg{kKidGemm64x64, 64, 64};
+            case kKidGemm256x160:  // fused gate/up only
+                if (a.epilogue == kEpiSwiglu && a.K % kBK == 0 && (a.N / 2) % 16 == 0)
+                    return TileCfg{kKidGemm256x160, 256, 160};
+                return TileCfg{kKidGemm256, 256, 256};
             case kKidGemm256x192:  // its fused gate/up epilogue exists on the direct-to-LDS kernel only
                 if (a.epilogue != kEpiSwiglu || (a.K % kBK == 0 && (a.N / 2) % 16 == 0))
                     return TileCfg{kKidGemm256x192, 256, 192};
@@ -1051,7 +1051,7 @@ bool deep_pipeline(const GemmArgs& a, const TileCfg& t) {
 // too few, and only when the workspace can hold the partials.
 int pick_splits(const GemmArgs& a, const TileCfg& t) {
     if (t.id == kKidGemm32 || t.id == kKidGemm64x64) return 1;
-    if (t.id == kKidGemm256x192 && a.epilogue == kEpiSwiglu) return 1;
+    if ((t.id == kKidGemm256x192 || t.id == kKidGemm256x160) && a.epilogue == kEpiSwiglu) return 1;
     const int tiles = ceil_div(a.M, t.bm) * ceil_div(a.N, t.bn);
     if (tiles >= 128 || a.K < 1024) return 1;  // half a chip of tiles: splitting costs more than it gains
     // one workgroup per CU with the deep pipeline, two otherwise
@@ -1075,7 +1075,7 @@ bool norm_fusable(const GemmArgs& a) {
            ((uintptr_t)a.norm_out % 8 == 0) && ((uintptr_t)a.norm_gain % 8 == 0);
 }
 
-template <int BM, int BN, int WM, int WN, int EPI, int SWIGLU, int DST = RPO_DMA_STAGES, int DBK = RPO_DMA_BK>
+template <int BM, int BN, int WM, int WN, int EPI, int SWIGLU, int DST = kDmaStages, int DBK = kDmaBK>
 hipError_t launch_one(const GemmArgs& a, int splits, void* out, hipStream_t s) {
     // direct-to-LDS pipeline shape: DBK-deep slabs in DST stages
     const int gm = ceil_div(a.M, BM), gn = ceil_div(a.N, BN);
@@ -1122,7 +1122,7 @@ hipError_t launch_one(const GemmArgs& a, int splits, void* out, hipStream_t s) {
     }
 }
 
-template <int BM, int BN, int WM, int WN, int DST = RPO_DMA_STAGES, int DBK = RPO_DMA_BK>
+template <int BM, int BN, int WM, int WN, int DST = kDmaStages, int DBK = kDmaBK>
 hipError_t launch_tile(const GemmArgs& a, int splits, hipStream_t s) {
     const bool sw = a.epilogue == kEpiSwiglu;
     constexpr bool kPairs = (BN / WN / 32) % 2 == 0;  // a wave holds gate/up block pairs
@@ -1243,8 +1243,6 @@ static hipError_t launch_gemm_only(const GemmArgs& a, int splits, const TileCfg&
     switch (t.id) {
         case kKidGemm256:
             return launch_tile<256, 256, 2, 4>(a, splits, s);
-        case kKidGemm256x128:
-            return launch_tile<256, 128, 2, 2>(a, splits, s);
         case kKidGemm128:
             if (deep_pipeline(a, t)) return launch_tile<128, 128, 2, 2, 4>(a, splits, s);
             return launch_tile<128, 128, 2, 2>(a, splits, s);
@@ -1257,6 +1255,8 @@ static hipError_t launch_gemm_only(const GemmArgs& a, int splits, const TileCfg&
             return launch_tile<32, 128, 1, 4, 4>(a, splits, s);
         case kKidGemm64x64:
             return launch_tile<64, 64, 2, 2, 4>(a, splits, s);
+        case kKidGemm256x160:
+            return launch_one<256, 160, 4, 1, kEpiSwiglu, 2>(a, 1, a.C, s);
         case kKidGemm256x192:
             if (a.epilogue == kEpiSwiglu) return launch_one<256, 192, 4, 2, kEpiSwiglu, 2>(a, 1, a.C, s);
             return launch_tile<256, 192, 4, 2>(a, splits, s);

@@ -88,7 +88,6 @@ enum KernelId : int {
     kKidNone = 0,
     // tile shapes of gemm_dma_kernel / gemm_mfma_kernel <BM, BN, waves along M, waves along N>
     kKidGemm256 = 1,        // <256,256,2,4> (many-tile problems)
-    kKidGemm256x128 = 2,    // <256,128,2,2> (tuning aid only)
     kKidGemm128 = 3,        // <128,128,2,2> (decode-sized problems with a deep K, K split)
     kKidGemm64 = 4,         // <64,128,1,2>  (the same for M <= 64)
     kKidGemm32 = 5,         // <32,128,1,4>  (decode QKV projection: one head per tile, no K split)
@@ -99,7 +98,8 @@ enum KernelId : int {
     kKidAttnChunk = 9,      // attn_chunk_mfma_kernel
     kKidSample = 10,        // sample_kernel
     kKidGemm256Swiglu = 12, // <256,256,2,4> with the fused SwiGLU epilogue (gate/up of prefill / log-prob chunks)
-    kKidCount = 13,
+    kKidGemm256x160 = 13,   // <256,160,4,1> fused SwiGLU only (decode gate/up: one round of workgroups on more CUs)
+    kKidCount = 14,
 };
 // Which kernel launch_gemm picks for these arguments.
 int gemm_kernel_id(const GemmArgs& a);
@@ -214,6 +214,16 @@ hipError_t launch_lse_combine(const float* part, int blocks, const float* target
                               int vocab, float inv_t, float* out, int rows, hipStream_t s);
 hipError_t launch_lse_gather(const float* logits, int64_t row_stride, int vocab, const int32_t* target,
                              float inv_t, float* out, int rows, hipStream_t s);
+
+// ---- experience cache (cache.hip) ----------------------------------------------
+hipError_t launch_cut_pack(const int32_t* prompts, int64_t prompt_stride, const int32_t* prompt_len,
+                           const int32_t* pool, int64_t pool_stride, const int32_t* question,
+                           const int32_t* cu_len, int n_groups, int32_t* out, hipStream_t s);
+hipError_t launch_cache_update(int32_t* pool, int64_t pool_stride, int32_t* answer_len, const int32_t* question,
+                               const int32_t* m,
+                               const int32_t* tokens, int64_t tok_stride, const int32_t* lengths,
+                               const float* rewards, const float* u, const int32_t* g_prime, int n_groups, int G,
+                               float eps, int32_t* chosen_out, hipStream_t s);
 
 hipError_t launch_objective(const float* lp_new, const float* lp_old, const float* lp_ref, const int32_t* cu,
                             const float* adv, int n_groups, int G, float eps_clip, float beta, float* tok_out,

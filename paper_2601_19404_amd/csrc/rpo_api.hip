@@ -51,8 +51,8 @@ extern "C" int rpo_probe_peaks(const void* src_dev, void* dst_dev, size_t bytes,
 }
 
 extern "C" int rpo_set_kernel_path(int path) {
-    if (path != 0 && path != 1 && path != 2 && !(path >= 17 && path <= 22) && path != 27)
-        return fail(RPO_EINVAL, "kernel path must be 0, 1, 2, 17..22 or 27");
+    if (path != 0 && path != 1 && path != 2 && path != 17 && !(path >= 19 && path <= 22) && path != 27 && path != 29)
+        return fail(RPO_EINVAL, "kernel path must be 0, 1, 2, 17, 19..22, 27 or 29");
     g_kernel_path = path;
     return RPO_OK;
 }
@@ -791,6 +791,66 @@ extern "C" int rpo_decode_step(rpo_batch* b, const int32_t* tokens_dev, int32_t 
 }
 
 // ---------------------------------------------------------------------------
+extern "C" int rpo_attn_decode(rpo_batch* b, int32_t layer, const void* q_dev, int32_t n_rows, int32_t n_suffix,
+                               const uint8_t* active_dev, void* out_dev, void* stream) {
+    if (!b || !q_dev || !out_dev) return fail(RPO_EINVAL, "rpo_attn_decode: NULL argument");
+    if (b->state != kForked) return fail(RPO_ESTATE, "rpo_attn_decode: call rpo_kv_fork first");
+    const BatchDims& bd = b->bd;
+    const rpo_model_desc& d = b->m->d;
+    if (layer < 0 || layer >= d.n_layers) return fail(RPO_EINVAL, "rpo_attn_decode: layer %d not in 0..%d", layer, d.n_layers - 1);
+    if (n_rows < 1 || n_rows > bd.B) return fail(RPO_EINVAL, "rpo_attn_decode: n_rows %d not in 1..%d", n_rows, bd.B);
+    if (n_suffix < 0 || n_suffix > bd.max_suffix)
+        return fail(RPO_EINVAL, "rpo_attn_decode: n_suffix %d not in 0..%d", n_suffix, bd.max_suffix);
+    for (int g = 0; g < ceil_div(n_rows, bd.G); ++g)
+        if (b->prefix_len[g] + n_suffix < 1) return fail(RPO_EINVAL, "rpo_attn_decode: empty context");
+    const WsLayout& L = b->L;
+    hipStream_t s = (hipStream_t)stream;
+    AttnArgs aa;
+    aa.q = q_dev;
+    aa.q_stride = (int64_t)d.n_q_heads * d.head_dim;
+    aa.out = out_dev;
+    aa.dtype = d.dtype;
+    aa.rows = n_rows;
+    aa.Hq = d.n_q_heads;
+    aa.Hkv = d.n_kv_heads;
+    aa.dh = d.head_dim;
+    aa.row_seq = nullptr;
+    aa.seqs = b->at<SeqDesc>(L.rollout_desc);
+    aa.n_seqs = n_rows;
+    aa.max_seq_rows = 1;
+    aa.pos_add = n_suffix - 1;  // a row sees positions [0, prefix_len + n_suffix)
+    aa.tables = b->at<int32_t>(L.tables);
+    aa.active = active_dev;
+    aa.kv_pool = b->kv;
+    aa.geom = b->geom;
+    aa.layer = layer;
+    aa.scale = 1.0f / sqrtf((float)d.head_dim);
+    aa.path = g_kernel_path;
+    DecodeAttnArgs da;
+    da.base = aa;
+    da.G = bd.G;
+    da.shared_pages = b->at<int32_t>(L.shared_pages);
+    int max_shared = 0;
+    double toks = 0.0, qk = 0.0;
+    for (int r = 0; r < n_rows; ++r) {
+        const int g = r / bd.G;
+        const int shared_tok = (b->prefix_len[g] / bd.pt) * bd.pt, ctx = b->prefix_len[g] + n_suffix;
+        max_shared = std::max(max_shared, b->prefix_len[g] / bd.pt);
+        toks += ctx - shared_tok;
+        if (r % bd.G == 0) toks += shared_tok;
+        qk += ctx;
+    }
+    da.max_shared_pages = max_shared;
+    da.max_own_pages = bd.ppr;
+    da.partial = b->at<float>(L.partial);
+    da.partial_floats = attn_decode_partial_floats(bd.B, d.n_q_heads, d.head_dim, bd.ppg);
+    HIP_TRY(timed(attn_uses_mfma(aa) ? kKidAttnDecode : 0, 4.0 * qk * d.n_q_heads * d.head_dim,
+                  toks * 2.0 * d.n_kv_heads * d.head_dim * dtype_size(d.dtype), s,
+                  [&] { return launch_attn_decode(da, s); }));
+    return RPO_OK;
+}
+
+// ---------------------------------------------------------------------------
 extern "C" int rpo_suffix_logprobs(rpo_batch* b, const int32_t* suffix_tokens_dev,
                                    const int32_t* cu_suffix_host, float temperature, float* logprobs_out_dev,
                                    void* stream) {
@@ -942,6 +1002,33 @@ extern "C" int rpo_shape_rewards(const float* rewards_dev, const int32_t* length
     if (!(alpha > 0.f) || !(lo <= hi)) return fail(RPO_EINVAL, "rpo_shape_rewards: need alpha > 0 and lo <= hi");
     HIP_TRY(launch_shape_rewards(rewards_dev, lengths_dev, n_groups, G, alpha, lo, hi, shaped_out_dev,
                                  (hipStream_t)stream));
+    return RPO_OK;
+}
+
+extern "C" int rpo_cut_pack(const int32_t* prompts_dev, int64_t prompt_stride, const int32_t* prompt_len_dev,
+                            const int32_t* pool_dev, int64_t pool_stride, const int32_t* question_dev,
+                            const int32_t* cu_len_dev, int32_t n_groups, int32_t* tokens_out_dev, void* stream) {
+    if (!prompts_dev || !prompt_len_dev || !pool_dev || !cu_len_dev || !tokens_out_dev)
+        return fail(RPO_EINVAL, "rpo_cut_pack: NULL argument");
+    if (n_groups < 0 || prompt_stride < 0 || pool_stride < 0) return fail(RPO_EINVAL, "rpo_cut_pack: bad sizes");
+    HIP_TRY(launch_cut_pack(prompts_dev, prompt_stride, prompt_len_dev, pool_dev, pool_stride, question_dev,
+                            cu_len_dev, n_groups, tokens_out_dev, (hipStream_t)stream));
+    return RPO_OK;
+}
+
+extern "C" int rpo_cache_update(int32_t* pool_dev, int64_t pool_stride, int32_t* answer_len_dev,
+                                const int32_t* question_dev, const int32_t* m_dev, const int32_t* tokens_dev, int64_t tok_stride,
+                                const int32_t* lengths_dev, const float* rewards_dev, const float* u_dev,
+                                const int32_t* g_prime_dev, int32_t n_groups, int32_t G, float eps,
+                                int32_t* chosen_out_dev, void* stream) {
+    if (!pool_dev || !answer_len_dev || !m_dev || !tokens_dev || !rewards_dev || !u_dev || !g_prime_dev)
+        return fail(RPO_EINVAL, "rpo_cache_update: NULL argument");
+    if (n_groups < 0 || G < 1 || pool_stride < 1 || tok_stride < 0)
+        return fail(RPO_EINVAL, "rpo_cache_update: bad sizes");
+    if (!(eps >= 0.f) || !(eps <= 1.f)) return fail(RPO_EINVAL, "rpo_cache_update: eps must be in [0, 1]");
+    HIP_TRY(launch_cache_update(pool_dev, pool_stride, answer_len_dev, question_dev, m_dev, tokens_dev, tok_stride, lengths_dev,
+                                rewards_dev, u_dev, g_prime_dev, n_groups, G, eps, chosen_out_dev,
+                                (hipStream_t)stream));
     return RPO_OK;
 }
 

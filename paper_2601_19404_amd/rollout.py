@@ -44,7 +44,7 @@ class RolloutResult:
 
 def suffix_rollout(batch: rpo.Batch, prompts, cached, m, temperature: float, seed: int,
                    seq_ids: torch.Tensor, keep_logits: bool | int = False, stream=None,
-                   marks: list | None = None, eos_id: int | None = None) -> RolloutResult:
+                   marks: list | None = None, eos_id: int | None = None, prefix=None) -> RolloutResult:
     """Regenerate m_k tokens for each of the G rollouts of every group.
 
     Groups must be ordered by decreasing m (see order_by_suffix_length) so that the
@@ -53,7 +53,9 @@ def suffix_rollout(batch: rpo.Batch, prompts, cached, m, temperature: float, see
     step's logits (tests), an integer n only those of the first n steps.  marks: if a list,
     (name, torch.cuda.Event) pairs are appended at the phase boundaries (benchmark timing).
     eos_id: if given, a rollout that samples it stops there (its later tokens are eos_id padding,
-    it appends no more K/V) and the per-rollout lengths are returned; m is then the cap."""
+    it appends no more K/V) and the per-rollout lengths are returned; m is then the cap.
+    prefix: (packed prefix tokens on the device, cu_len host array) when the cut was already made
+    on the device (DeviceCachePool.cut_pack); prompts / cached are then not read."""
     cfg = batch.model.cfg
     G, ng = batch.G, batch.n_groups
     B = ng * G
@@ -61,8 +63,11 @@ def suffix_rollout(batch: rpo.Batch, prompts, cached, m, temperature: float, see
     if len(m) != ng or np.any(np.diff(m) > 0):
         raise ValueError("groups must be ordered by decreasing suffix length")
     V = cfg.vocab
-    toks_host, cu = cut_and_pack(prompts, cached, m)
-    tokens_dev = torch.from_numpy(toks_host).cuda()
+    if prefix is not None:
+        tokens_dev, cu = prefix
+    else:
+        toks_host, cu = cut_and_pack(prompts, cached, m)
+        tokens_dev = torch.from_numpy(toks_host).cuda()
     max_m = int(m.max()) if ng else 0
     last_logits = torch.empty((ng, V), dtype=torch.float32, device="cuda")
     logits = torch.empty((B, V), dtype=torch.float32, device="cuda")

@@ -87,8 +87,10 @@ def _slice_parity(cfg, n_steps, max_rows, check_fraction=True):
     live = np.arange(toks.shape[1])[None, :] < np.repeat(m, G)[:, None]
     assert np.all(np.isfinite(slp[live])) and np.all(slp[live] <= 0)
     # one policy scores its own samples: the teacher-forced log-probs equal the sampler's
+    # (two routes through the kernels, each carrying its own share of the bf16 quantisation noise:
+    # judged against the measured floor further down)
     lp_packed = np.concatenate([slp[r, :int(m[r // G])] for r in range(ng * G)])
-    assert np.sqrt(np.mean((lp_gpu - lp_packed) ** 2)) < 4e-2
+    two_route_rms = float(np.sqrt(np.mean((lp_gpu - lp_packed) ** 2)))
 
     g = ng - 1                                              # the group with the shortest suffix
     kept = [k.cpu().numpy() for k in res.logits]
@@ -129,6 +131,9 @@ def _slice_parity(cfg, n_steps, max_rows, check_fraction=True):
           f"x{err_max / floor_max:.2f})", flush=True)
     assert err_rms <= FLOOR_RMS * floor_rms and err_max <= FLOOR_MAX * floor_max
     assert err_rms < 0.05 * sd
+    print(f"decode-loop vs teacher-forced log-probs over all {len(lp_gpu)} tokens: rms {two_route_rms:.3e} "
+          f"(x{two_route_rms / floor_rms:.2f} of the floor rms)", flush=True)
+    assert two_route_rms <= 3.0 * floor_rms
 
     # integer contract on the GPU's own logits rows
     t, _ = osampler.sample(kept[0], cfg.temperature, 3, sid, 0, row_map=np.zeros(G, np.int64))

@@ -1,4 +1,4 @@
-"""GPU parity of the stand-alone entry points: GEMM, sampler, advantages.
+"""GPU parity of the stand-alone entry points: GEMM, decode attention, sampler, advantages.
 Every call goes through the C ABI (paper_2601_19404_amd.binding)."""
 import numpy as np
 import pytest
@@ -7,6 +7,8 @@ import torch
 from oracle import advantages as oadv
 from oracle import sampler as osampler
 from oracle import transformer as T
+from paper_2601_19404_amd import synth
+from tests import util
 
 pytestmark = pytest.mark.gpu
 
@@ -64,7 +66,7 @@ def test_gemm_mfma_bf16_model_shapes(rpo, shape, ws_mb):
         _gemm_case(rpo, *shape, torch.bfloat16, epi, path=0, seed=3, ws_mb=ws_mb)
 
 
-@pytest.mark.parametrize("path", [17, 18, 19, 20, 21, 22, 27])
+@pytest.mark.parametrize("path", [17, 19, 20, 21, 22, 27])
 @pytest.mark.parametrize("shape", [(300, 520, 1536), (77, 1536, 4480)])
 def test_gemm_mfma_bf16_every_tile_shape(rpo, shape, path):
     """Each tile shape forced in turn (16 + kernel id), with and without a K-split workspace."""
@@ -288,3 +290,71 @@ def test_profile_sampling_and_peak_probe(rpo):
     copy_gbps, mfma_tflops = rpo.rpo_probe_peaks(1 << 28)
     assert 500.0 < copy_gbps < 8000.0                 # below the published HBM peak
     assert 200.0 < mfma_tflops < 2500.0               # below the published bf16 MFMA peak
+
+
+# ---------------------------------------------------------------------------
+def _attn_decode_case(rpo, mcfg, prefix_lens, G, n_fill, suffix_views, check_groups, seed):
+    """rpo_attn_decode (the shared-prefix decode attention of one layer, alone) against the plain
+    softmax(q K^T / sqrt(dh)) V of the oracle.  The pages are filled by a real prefill + fork and
+    n_fill decode steps on fixed tokens; the oracle builds the same keys / values (bf16 cache) with
+    its own forward; the queries are random."""
+    from paper_2601_19404_amd import rollout
+    rng = np.random.default_rng(seed)
+    w = synth.perturb_gains(synth.make_weights(mcfg, seed=seed))
+    w_np = synth.weights_to_numpy(w)
+    shape_q = util.oracle_shape(mcfg, storage="model")
+    model = rpo.rpo_model_create(mcfg, util.to_device(w))
+    ng = len(prefix_lens)
+    B = ng * G
+    prefixes = [rng.integers(0, mcfg.vocab, size=n).astype(np.int32) for n in prefix_lens]
+    cu = np.concatenate([[0], np.cumsum(prefix_lens)]).astype(np.int32)
+    batch = rpo.rpo_batch_create(model, ng, G, int(max(prefix_lens)), max(n_fill, 1), 64,
+                                 max(int(sum(prefix_lens)), B, 1024))
+    last = torch.empty(ng, mcfg.vocab, device="cuda")
+    rpo.rpo_prefill_prefix(batch, torch.from_numpy(np.concatenate(prefixes)).cuda(), cu, last)
+    rpo.rpo_kv_fork(batch)
+    logits = torch.empty(B, mcfg.vocab, device="cuda")
+    step_tok = lambda j: ((np.arange(B) * 7 + 13 * j) % mcfg.vocab).astype(np.int32)
+    for j in range(n_fill):
+        rpo.rpo_decode_step(batch, torch.from_numpy(step_tok(j)).cuda(), B, None, logits)
+    width = mcfg.n_q_heads * mcfg.head_dim
+    q = (torch.randn(B, width, generator=torch.Generator().manual_seed(seed)) * 1.5).to(torch.bfloat16)
+    q_dev = q.cuda()
+    q64 = q.float().numpy().astype(np.float64).reshape(B, mcfg.n_q_heads, mcfg.head_dim)
+    worst = 0.0
+    for n_suffix in suffix_views:
+        out = torch.full((B, width), 7.0, dtype=torch.bfloat16, device="cuda")
+        rpo.rpo_attn_decode(batch, 0, q_dev, B, n_suffix, None, out)
+        torch.cuda.synchronize()
+        got = out.float().cpu().numpy().reshape(B, mcfg.n_q_heads, mcfg.head_dim)
+        for g in check_groups:
+            kv0, _ = T.prefill(shape_q, w_np, prefixes[g])
+            for i in (0, G - 1):
+                r = g * G + i
+                kv = kv0.copy()
+                for j in range(n_suffix):
+                    T.decode_step(shape_q, w_np, int(step_tok(j)[r]), kv)
+                ctx = prefix_lens[g] + n_suffix
+                ref = T.attention_rows(shape_q, q64[r:r + 1], kv.k[0][:ctx], kv.v[0][:ctx], np.ones((1, ctx), bool))[0]
+                err = np.abs(got[r] - ref).max() / np.abs(ref).max()
+                worst = max(worst, float(err))
+    print(f"decode attention alone vs oracle: max error {worst:.3e} of the output scale", flush=True)
+    # bf16 output (2^-9), bf16 probabilities in the second product, bf16 K/V computed by two pipelines
+    assert worst < 2e-2
+
+
+def test_attn_decode_alone_small(rpo):
+    mcfg = synth.ModelCfg("attn-1layer", 1, 768, 6, 1, 128, 256, 512, "bf16")
+    _attn_decode_case(rpo, mcfg, prefix_lens=(300, 257, 640, 64, 130, 20), G=8, n_fill=70,
+                      suffix_views=(0, 1, 37, 70), check_groups=(0, 2, 3, 5), seed=61)
+
+
+def test_attn_decode_alone_benchmark_shape(rpo):
+    """The 1.5B benchmark's attention launch: 64 groups x 8 rollouts, 12 q / 2 kv heads, ~2000-token
+    shared prefixes (31-32 shared pages per group, four prefix pieces per group and KV head), 150
+    private tokens per rollout; two groups recomputed by the oracle."""
+    mcfg = synth.ModelCfg("attn-1layer-c1", 1, 1536, 12, 2, 128, 256, 512, "bf16")
+    wl = synth.make_workload(synth.C1)
+    lens = tuple(int(synth.C1.prompt_len + synth.C1.traj_len - mk) for mk in wl.m)
+    _attn_decode_case(rpo, mcfg, prefix_lens=lens, G=8, n_fill=150, suffix_views=(150,), check_groups=(0, 63),
+                      seed=62)
