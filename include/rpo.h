@@ -143,6 +143,26 @@ int rpo_kv_fork(rpo_batch *b, void *stream);
 int rpo_decode_step(rpo_batch *b, const int32_t *tokens_dev, int32_t n_rows,
                     const uint8_t *active_dev, float *logits_dev, float *row_max_out_dev, void *stream);
 
+/* rpo_decode_step over a COMPACTED batch, for variable-length rollouts (the paper generates until
+ * end-of-sequence or the length cap, Sec. 4.1): rollouts that have finished leave the batch
+ * instead of being masked, so the projections and the LM head run on the live rows only.
+ * A small kernel lists the live rollouts of rows [0, n_rows) (active != 0) in increasing order;
+ * query row c of the step belongs to the c-th of them.
+ *   active_dev      device uint8 [n_rows], required (rpo_sample's active_inout_dev)
+ *   logits_dev      device fp32 [n_rows, vocab]: row c scores the next token of the c-th live
+ *                   rollout; rows beyond the live ones hold unspecified values
+ *   row_max_out_dev device fp32 [n_rows] or NULL, indexed like logits_dev
+ *   row_of_out_dev  device int32 [n_rows]: logits row of rollout r, -1 if it has finished -- pass it
+ *                   to rpo_sample as row_map_dev (with n_logit_rows = *n_logit_rows_out)
+ *   n_logit_rows_out host int32: logits rows this step computed.  It is the number of live
+ *                   rollouts the device last REPORTED to the host (through a pinned word, without
+ *                   any wait), hence an upper bound of the live rows of this step that trails the
+ *                   true count by the steps still in flight; 0 once every rollout has finished.
+ * Everything else as rpo_decode_step.  Errors: RPO_ESTATE, RPO_EINVAL. */
+int rpo_decode_step_compact(rpo_batch *b, const int32_t *tokens_dev, int32_t n_rows, const uint8_t *active_dev,
+                            float *logits_dev, float *row_max_out_dev, int32_t *row_of_out_dev,
+                            int32_t *n_logit_rows_out, void *stream);
+
 /* Draw one token per output row from softmax(logits / temperature) (the paper
  * samples with a temperature, Sec. 4.1).  Stateless.  The draw is defined through
  * integers so that it does not depend on reduction order (bit-exact contract):

@@ -67,6 +67,7 @@ def lib() -> C.CDLL:
     L.rpo_prefill_prefix.argtypes = [vp, vp, C.POINTER(i32), vp, vp]
     L.rpo_kv_fork.argtypes = [vp, vp]
     L.rpo_decode_step.argtypes = [vp, vp, i32, vp, vp, vp, vp]
+    L.rpo_decode_step_compact.argtypes = [vp, vp, i32, vp, vp, vp, vp, C.POINTER(i32), vp]
     L.rpo_sample.argtypes = [vp, i32, i32, i64, vp, i32, f32, u64, vp, u32, vp, vp, i32, vp, vp, vp, vp]
     L.rpo_suffix_logprobs.argtypes = [vp, vp, C.POINTER(i32), f32, vp, vp]
     L.grpo_advantages.argtypes = [vp, i32, i32, i32, f32, vp, vp]
@@ -83,7 +84,7 @@ def lib() -> C.CDLL:
     L.rpo_profile_stop.argtypes = [C.c_int, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(C.c_double),
                                    C.POINTER(C.c_double)]
     for name in ("rpo_model_create", "rpo_batch_create", "rpo_prefill_prefix", "rpo_kv_fork",
-                 "rpo_decode_step", "rpo_sample", "rpo_suffix_logprobs", "grpo_advantages",
+                 "rpo_decode_step", "rpo_decode_step_compact", "rpo_sample", "rpo_suffix_logprobs", "grpo_advantages",
                  "rpo_shape_rewards", "rpo_objective_forward", "rpo_cut_pack", "rpo_cache_update", "rpo_gemm_nt",
                  "rpo_attn_decode", "rpo_gemm_nt_noalloc", "rpo_set_kernel_path", "rpo_profile_start", "rpo_profile_stop", "rpo_probe_peaks"):
         getattr(L, name).restype = C.c_int
@@ -93,7 +94,7 @@ def lib() -> C.CDLL:
 
 EXPORTS = ("rpo_model_create", "rpo_model_destroy", "rpo_kv_pool_bytes", "rpo_workspace_bytes",
            "rpo_batch_create", "rpo_batch_destroy", "rpo_prefill_prefix", "rpo_kv_fork",
-           "rpo_decode_step", "rpo_sample", "rpo_suffix_logprobs", "grpo_advantages",
+           "rpo_decode_step", "rpo_decode_step_compact", "rpo_sample", "rpo_suffix_logprobs", "grpo_advantages",
            "rpo_shape_rewards", "rpo_objective_forward", "rpo_cut_pack", "rpo_cache_update", "rpo_last_error", "rpo_gemm_nt", "rpo_attn_decode", "rpo_gemm_nt_noalloc", "rpo_set_kernel_path", "rpo_profile_start",
            "rpo_profile_stop", "rpo_probe_peaks")
 
@@ -234,6 +235,25 @@ def rpo_decode_step(batch: Batch, tokens_dev: torch.Tensor, n_rows: int, active_
         raise ValueError("row_max_out_dev must be float32 with at least n_rows elements")
     _check(lib().rpo_decode_step(batch.handle, tokens_dev.data_ptr(), n_rows, _ptr(active_dev),
                                  logits_dev.data_ptr(), _ptr(row_max_out_dev), _stream(stream)))
+
+
+def rpo_decode_step_compact(batch: Batch, tokens_dev: torch.Tensor, n_rows: int, active_dev: torch.Tensor,
+                            logits_dev: torch.Tensor, row_of_out_dev: torch.Tensor, stream=None,
+                            row_max_out_dev=None) -> int:
+    """rpo_decode_step on the live rollouts only; returns the number of logits rows computed."""
+    if tokens_dev.numel() < n_rows or logits_dev.numel() < n_rows * batch.model.cfg.vocab:
+        raise ValueError("tokens_dev / logits_dev smaller than n_rows")
+    if active_dev is None or active_dev.dtype != torch.uint8 or active_dev.numel() < n_rows:
+        raise ValueError("active_dev must be uint8 with at least n_rows elements")
+    if row_of_out_dev.dtype != torch.int32 or row_of_out_dev.numel() < n_rows:
+        raise ValueError("row_of_out_dev must be int32 with at least n_rows elements")
+    if row_max_out_dev is not None and (row_max_out_dev.dtype != torch.float32 or row_max_out_dev.numel() < n_rows):
+        raise ValueError("row_max_out_dev must be float32 with at least n_rows elements")
+    n = C.c_int32(0)
+    _check(lib().rpo_decode_step_compact(batch.handle, tokens_dev.data_ptr(), n_rows, active_dev.data_ptr(),
+                                         logits_dev.data_ptr(), _ptr(row_max_out_dev), row_of_out_dev.data_ptr(),
+                                         C.byref(n), _stream(stream)))
+    return n.value
 
 
 def rpo_sample(logits_dev: torch.Tensor, n_logit_rows: int, vocab: int, row_stride: int, row_map_dev,

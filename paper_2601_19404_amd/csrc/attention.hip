@@ -35,8 +35,9 @@ __global__ __launch_bounds__(64) void attn_generic_kernel(AttnArgs a) {
     const int r = blockIdx.x, hq = blockIdx.y, lane = threadIdx.x;
     if (a.active && !a.active[r]) return;
     const int seq = a.row_seq ? a.row_seq[r] : r;
+    if (seq < 0) return;  // padding row of a compacted batch
     const SeqDesc sd = a.seqs[seq];
-    const int ctx = sd.pos0 + (r - sd.row_start) + a.pos_add + 1;
+    const int ctx = sd.pos0 + (a.single_row ? 0 : r - sd.row_start) + a.pos_add + 1;
     const int kh = hq / (a.Hq / a.Hkv);
     const int dh = a.dh, pt = a.geom.page_tokens;
     const T* q = (const T*)a.q + (int64_t)r * a.q_stride + (int64_t)hq * dh;
@@ -347,7 +348,8 @@ __global__ __launch_bounds__(256, 2) void attn_chunk_mfma_kernel(AttnArgs a) {
 // ---------------------------------------------------------------------------
 struct DecodeGeom {
     int G, n_split, n_ct, rpt;  // rollouts per column tile
-    int n_rows;                 // live rollout rows
+    int n_rows;                 // rollout rows covered (r = group * G + i < n_rows)
+    const int32_t* row_of;      // compacted batch: rollout -> query / output row (< 0: finished), or NULL
 };
 
 __global__ __launch_bounds__(256) void attn_decode_mfma_kernel(AttnArgs a, DecodeGeom dg,
@@ -386,16 +388,22 @@ __global__ __launch_bounds__(256) void attn_decode_mfma_kernel(AttnArgs a, Decod
         piece = dg.n_split;
         trow = grp * dg.G + ri;
     }
+    // a rollout is live if it has a query row: its row in a compacted batch, else its active flag
+    auto query_row = [&](int rollout) -> int {
+        if (rollout >= dg.n_rows) return -1;
+        if (dg.row_of) return dg.row_of[rollout];
+        return (a.active && !a.active[rollout]) ? -1 : rollout;
+    };
     const bool trow_ok = trow < dg.n_rows;
     const SeqDesc sd = a.seqs[trow_ok ? trow : 0];
     const int ctx = sd.pos0 + a.pos_add + 1;  // the same for every rollout of a group
-    if (part >= n_pref && trow_ok && !(a.active && !a.active[trow])) page_end = (ctx + kPt - 1) / kPt;
+    if (part >= n_pref && query_row(trow) >= 0) page_end = (ctx + kPt - 1) / kPt;
     if (!trow_ok) page_end = page_begin;
-    const int row = grp * dg.G + ri;
-    bool valid = col_ok && row < dg.n_rows;
-    if (valid && a.active && !a.active[row]) valid = false;
+    const int row = grp * dg.G + ri;          // rollout
+    const int qrow = col_ok ? query_row(row) : -1;
+    const bool valid = qrow >= 0;
     const int head = kh * hpk + col % hpk;
-    const bf16* const qptr[1] = {valid ? (const bf16*)a.q + (int64_t)row * a.q_stride + (int64_t)head * kDh : nullptr};
+    const bf16* const qptr[1] = {valid ? (const bf16*)a.q + (int64_t)qrow * a.q_stride + (int64_t)head * kDh : nullptr};
     const int limit[1] = {valid ? ctx : 0};
 
     AttnState<1> st;
@@ -416,12 +424,16 @@ __global__ __launch_bounds__(256) void attn_decode_mfma_kernel(AttnArgs a, Decod
 // One workgroup per rollout row, one thread per (query head, pair of output channels): combine
 // the pieces.  All loads of a thread are issued before any is used (at most kMaxPieces pieces).
 constexpr int kMaxPieces = 9;  // decode_splits() caps the prefix pieces at 8, plus the private one
+// Query row blockIdx.x belongs to rollout row_seq[blockIdx.x] (compacted batch; < 0: padding) or to
+// the rollout of the same index; the pieces are stored by rollout.
 __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict__ part_o,
                                                          const float* __restrict__ part_ml, int n_pieces,
                                                          int Hq, const uint8_t* __restrict__ active,
+                                                         const int32_t* __restrict__ row_seq,
                                                          bf16* __restrict__ out) {
-    const int row = blockIdx.x;
-    if (active && !active[row]) return;
+    const int qrow = blockIdx.x;
+    const int row = row_seq ? row_seq[qrow] : qrow;
+    if (row < 0 || (!row_seq && active && !active[row])) return;
     for (int w = threadIdx.x; w < Hq * (kDh / 2); w += 256) {
         const int head = w / (kDh / 2), c = (w % (kDh / 2)) * 2;
         const int64_t base = ((int64_t)row * Hq + head) * n_pieces;
@@ -446,7 +458,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(const float* __restrict
             o1 += wgt * o[p].y;
         }
         const float inv = 1.0f / lsum;
-        bf16* dst = out + ((int64_t)row * Hq + head) * kDh + c;
+        bf16* dst = out + ((int64_t)qrow * Hq + head) * kDh + c;
         dst[0] = f32_to_bf16(o0 * inv);
         dst[1] = f32_to_bf16(o1 * inv);
     }
@@ -502,10 +514,11 @@ hipError_t launch_attn_decode(const DecodeAttnArgs& d, hipStream_t s) {
     dg.G = d.G;
     dg.rpt = 64 / hpk < d.G ? 64 / hpk : d.G;
     dg.n_ct = ceil_div(d.G, dg.rpt);
-    dg.n_rows = a.rows;
-    const int n_groups_live = ceil_div(a.rows, d.G);
+    dg.n_rows = d.n_rollouts;
+    dg.row_of = d.row_of;
+    const int n_groups_live = ceil_div(d.n_rollouts, d.G);
     dg.n_split = decode_splits(n_groups_live, a.Hkv, dg.n_ct, d.max_shared_pages);
-    const size_t n_slots = (size_t)a.rows * a.Hq * (dg.n_split + 1);
+    const size_t n_slots = (size_t)d.n_rollouts * a.Hq * (dg.n_split + 1);
     if (n_slots * (kDh + 2) > d.partial_floats) return hipErrorInvalidValue;
     float* part_o = d.partial;
     float* part_ml = d.partial + n_slots * kDh;
@@ -517,7 +530,8 @@ hipError_t launch_attn_decode(const DecodeAttnArgs& d, hipStream_t s) {
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (dg.n_split + 1 > kMaxPieces) return hipErrorInvalidValue;
-    attn_merge_kernel<<<a.rows, 256, 0, s>>>(part_o, part_ml, dg.n_split + 1, a.Hq, a.active, (bf16*)a.out);
+    attn_merge_kernel<<<a.rows, 256, 0, s>>>(part_o, part_ml, dg.n_split + 1, a.Hq, a.active,
+                                             d.row_of ? a.row_seq : nullptr, (bf16*)a.out);
     return hipGetLastError();
 }
 

@@ -11,7 +11,8 @@ __global__ __launch_bounds__(256) void embed_kernel(const int32_t* __restrict__ 
                                                     const T* __restrict__ embed, int vocab, int d,
                                                     float* __restrict__ x) {
     const int r = blockIdx.x;
-    const int tok = tokens[tok_index ? tok_index[r] : r];
+    const int idx = tok_index ? tok_index[r] : r;
+    const int tok = idx >= 0 ? tokens[idx] : -1;
     const bool ok = tok >= 0 && tok < vocab;
     const T* src = embed + (int64_t)(ok ? tok : 0) * d;
     float* dst = x + (int64_t)r * d;
@@ -173,8 +174,9 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(RopeKvArgs a) {
     const int r = blockIdx.x;
     if (a.active && !a.active[r]) return;
     const int seq = a.row_seq ? a.row_seq[r] : r;
+    if (seq < 0) return;
     const SeqDesc sd = a.seqs[seq];
-    const int pos = sd.pos0 + (r - sd.row_start) + a.pos_add;
+    const int pos = sd.pos0 + (a.single_row ? 0 : r - sd.row_start) + a.pos_add;
     const int pt = a.geom.page_tokens;
     const int64_t page = a.tables[sd.table_off + pos / pt];
     const int slot = pos % pt;
@@ -217,6 +219,55 @@ hipError_t launch_rope_kv(const RopeKvArgs& a, hipStream_t s) {
         rope_kv_kernel<float><<<a.rows, 256, 0, s>>>(a);
     else
         rope_kv_kernel<bf16><<<a.rows, 256, 0, s>>>(a);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// One workgroup of 1024 threads; thread t owns rows [t * per, (t + 1) * per).
+__global__ __launch_bounds__(1024) void compact_rows_kernel(const uint8_t* __restrict__ active, int n_rows,
+                                                            int32_t* __restrict__ live, int32_t* __restrict__ row_of,
+                                                            int32_t* __restrict__ count_dev,
+                                                            uint64_t* __restrict__ mailbox, uint32_t generation) {
+    __shared__ int wave_tot[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int per = (n_rows + 1023) / 1024;
+    const int r0 = min(n_rows, tid * per), r1 = min(n_rows, r0 + per);
+    int mine = 0;
+    for (int r = r0; r < r1; ++r) mine += active[r] != 0;
+    // exclusive prefix over the 1024 threads: inside a wave by shuffles, across waves through LDS
+    int incl = mine;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int v = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += v;
+    }
+    if (lane == 63) wave_tot[wave] = incl;
+    __syncthreads();
+    int base = 0, total = 0;
+    for (int w = 0; w < 16; ++w) {
+        if (w < wave) base += wave_tot[w];
+        total += wave_tot[w];
+    }
+    int c = base + incl - mine;
+    for (int r = r0; r < r1; ++r) {
+        if (active[r] != 0) {
+            live[c] = r;
+            row_of[r] = c++;
+        } else {
+            row_of[r] = -1;
+        }
+    }
+    for (int k = total + tid; k < n_rows; k += 1024) live[k] = -1;
+    if (tid == 0) {
+        *count_dev = total;
+        if (mailbox) *(volatile uint64_t*)mailbox = ((uint64_t)generation << 32) | (uint32_t)total;
+    }
+}
+
+hipError_t launch_compact_rows(const uint8_t* active, int n_rows, int32_t* live, int32_t* row_of,
+                               int32_t* count_dev, uint64_t* mailbox, uint32_t generation, hipStream_t s) {
+    if (n_rows <= 0) return hipSuccess;
+    compact_rows_kernel<<<1, 1024, 0, s>>>(active, n_rows, live, row_of, count_dev, mailbox, generation);
     return hipGetLastError();
 }
 

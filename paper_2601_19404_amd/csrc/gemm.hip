@@ -19,6 +19,8 @@
 //    multiple of 64 (and selectable for comparison).
 //  * gemm_generic_kernel: any dtype on the vector ALUs (fp32 tiny model, shapes the
 //    MFMA kernels do not take).
+#include <stdlib.h>
+
 #include "kernels.hpp"
 
 namespace rpo {
@@ -756,10 +758,10 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const bf16* __res
             const int r = m0 + tid;
             int pos = -1;
             int64_t page = 0;
-            if (r < M && !(rk.active && !rk.active[r])) {
-                const int seq = rk.row_seq ? rk.row_seq[r] : r;
+            const int seq = r < M ? (rk.row_seq ? rk.row_seq[r] : r) : -1;
+            if (seq >= 0 && !(rk.active && !rk.active[r])) {
                 const SeqDesc sd = rk.seqs[seq];
-                pos = sd.pos0 + (r - sd.row_start) + rk.pos_add;
+                pos = sd.pos0 + (rk.single_row ? 0 : r - sd.row_start) + rk.pos_add;
                 page = rk.tables[sd.table_off + pos / rk.geom.page_tokens];
             }
             row_pos[tid] = pos;
@@ -930,13 +932,13 @@ __global__ __launch_bounds__(256) void gemm_splitk_reduce_rope_kernel(const floa
     __syncthreads();
     bf16* row = (bf16*)a.qkv + (int64_t)r * N;
     const int dh = a.dh, half = dh / 2;
-    if (a.active && !a.active[r]) {  // finished rollout: keep q defined, append nothing
+    const int seq = a.row_seq ? a.row_seq[r] : r;
+    if (seq < 0 || (a.active && !a.active[r])) {  // finished rollout / padding row: keep q defined, append nothing
         for (int c = tid; c < a.Hq * dh; c += 256) row[c] = f32_to_bf16(rowsum[c]);
         return;
     }
-    const int seq = a.row_seq ? a.row_seq[r] : r;
     const SeqDesc sd = a.seqs[seq];
-    const int pos = sd.pos0 + (r - sd.row_start) + a.pos_add;
+    const int pos = sd.pos0 + (a.single_row ? 0 : r - sd.row_start) + a.pos_add;
     const int pt = a.geom.page_tokens;
     const int64_t page = a.tables[sd.table_off + pos / pt];
     const int slot = pos % pt;
@@ -1016,8 +1018,14 @@ TileCfg pick_tile(const GemmArgs& a) {
     // The gate/up projection of a decode step: one round of fewer 256x256 tiles than CUs; 256x192
     // tiles still fit one round and each is a quarter cheaper.
     if (a.epilogue == kEpiSwiglu && a.M > 128 && t256 >= 128 && t256 <= 256 && a.K % kBK == 0 && a.path != 2 &&
-        (a.N / 2) % 16 == 0 && ceil_div(a.M, 256) * ceil_div(a.N, 192) <= 256)
+        (a.N / 2) % 16 == 0 && ceil_div(a.M, 256) * ceil_div(a.N, 192) <= 256) {
+        // 256x160 tiles (four waves of 64x160) still fit one round and put work on more CUs.  Measured:
+        // they win once K is deep enough for the main loop to outweigh the longer per-wave prologue and
+        // epilogue (K = 3584, N = 37888: 90 -> 81 us at 256 rows, 192 -> 149 us at 512 rows; K = 1536:
+        // 39.5 -> 40.2 us at 512 rows).
+        if (a.K >= 2048 && ceil_div(a.M, 256) * ceil_div(a.N, 160) <= 256) return TileCfg{kKidGemm256x160, 256, 160};
         return TileCfg{kKidGemm256x192, 256, 192};
+    }
     // up to 128 rows a 256-row tile multiplies mostly padding
     if (a.epilogue == kEpiSwiglu && a.M > 64 && a.M <= 128 && t256 >= 128) return TileCfg{kKidGemm128, 128, 128};
     if (a.M > 512 || (a.M > 64 && t256 >= 128)) {
@@ -1123,11 +1131,11 @@ hipError_t launch_one(const GemmArgs& a, int splits, void* out, hipStream_t s) {
 }
 
 template <int BM, int BN, int WM, int WN, int DST = kDmaStages, int DBK = kDmaBK>
-hipError_t launch_tile(const GemmArgs& a, int splits, hipStream_t s) {
+hipError_t launch_tile(const GemmArgs& a, int splits, hipStream_t s, bool via_ws = false) {
     const bool sw = a.epilogue == kEpiSwiglu;
     constexpr bool kPairs = (BN / WN / 32) % 2 == 0;  // a wave holds gate/up block pairs
     if (sw && !kPairs) return hipErrorInvalidValue;
-    if (splits > 1) {
+    if (splits > 1 || via_ws) {
         hipError_t e;
         if constexpr (kPairs) {
             e = sw ? launch_one<BM, BN, WM, WN, kEpiPartial, true, DST, DBK>(a, splits, a.ws, s)
@@ -1239,6 +1247,15 @@ int gemm_kernel_id(const GemmArgs& a) {
     return (id == kKidGemm256 && a.epilogue == kEpiSwiglu) ? (int)kKidGemm256Swiglu : id;
 }
 
+// The output projection of a decode step (64x64 tiles, no K split) followed by an RMSNorm: the
+// tiles write their fp32 result to the workspace and the reduction kernel adds the residual and
+// normalises, instead of a read-modify-write epilogue followed by a stand-alone RMSNorm launch.
+static bool norm_via_workspace(const GemmArgs& a, const TileCfg& t) {
+    static const bool on = getenv("RPO_EXP_NORM_WS") != nullptr;
+    return on && t.id == kKidGemm64x64 && a.epilogue == kEpiAddF32 && a.norm_out && norm_fusable(a) && a.ws &&
+           (size_t)a.M * a.N * sizeof(float) <= a.ws_bytes && a.K % kBK == 0 && a.path != 2;
+}
+
 static hipError_t launch_gemm_only(const GemmArgs& a, int splits, const TileCfg& t, hipStream_t s) {
     switch (t.id) {
         case kKidGemm256:
@@ -1254,7 +1271,7 @@ static hipError_t launch_gemm_only(const GemmArgs& a, int splits, const TileCfg&
             }
             return launch_tile<32, 128, 1, 4, 4>(a, splits, s);
         case kKidGemm64x64:
-            return launch_tile<64, 64, 2, 2, 4>(a, splits, s);
+            return launch_tile<64, 64, 2, 2, 4>(a, splits, s, norm_via_workspace(a, t));
         case kKidGemm256x160:
             return launch_one<256, 160, 4, 1, kEpiSwiglu, 2>(a, 1, a.C, s);
         case kKidGemm256x192:
@@ -1288,7 +1305,7 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
             return launch_one<256, 256, 2, 4, kEpiLogitsMax, false>(a, 1, a.C, s);
         }
         e = launch_gemm_only(a, splits, t, s);
-        norm_done = want_norm && splits > 1 && norm_fusable(a);  // fused into the K-split reduction
+        norm_done = want_norm && (splits > 1 || norm_via_workspace(a, t)) && norm_fusable(a);  // fused into the reduction
         rope_done = (splits > 1 && rope_fusable(a)) || (t.id == kKidGemm32 && rope_direct(a));
     }
     if (e != hipSuccess) return e;

@@ -109,7 +109,7 @@ size_t gemm_splitk_scratch_bytes(const GemmArgs& a);
 
 // ---- elementwise ---------------------------------------------------------------
 // x[r, :] = embed[tokens[idx(r)], :] as fp32, idx(r) = tok_index ? tok_index[r] : r;
-// out-of-range ids give a zero row.
+// out-of-range ids and idx(r) < 0 give a zero row.
 hipError_t launch_embed(const int32_t* tokens, const int32_t* tok_index, const void* embed, int dtype,
                         int vocab, int d, float* x, int rows, hipStream_t s);
 // h[r, :] = x[src(r), :] / sqrt(mean(x^2) + eps) * gain, src(r) = row_idx ? row_idx[r] : r.
@@ -129,9 +129,11 @@ struct RopeKvArgs {
     int rows;
     int Hq, Hkv, dh;
     const float* rope;      // [max_pos, dh/2, 2] (cos, sin)
-    const int32_t* row_seq;  // row -> sequence index, or NULL: sequence = row
+    const int32_t* row_seq;  // row -> sequence index (< 0: a padding row, nothing is written), or NULL: sequence = row
     const SeqDesc* seqs;
     int pos_add;             // added to every position (decode step)
+    int single_row = 0;      // 1: every row is THE row of its sequence (position pos0 + pos_add) wherever it
+                             // sits in the row buffer (decode step over a compacted batch)
     const int32_t* tables;
     const uint8_t* active;  // per row, or NULL
     void* kv_pool;
@@ -155,7 +157,8 @@ struct AttnArgs {
     int dtype;
     int rows;
     int Hq, Hkv, dh;
-    const int32_t* row_seq;  // or NULL: sequence = row
+    const int32_t* row_seq;  // or NULL: sequence = row; < 0: a padding row (skipped)
+    int single_row = 0;      // as in RopeKvArgs
     const SeqDesc* seqs;
     int n_seqs;
     int max_seq_rows;  // largest n_rows among seqs (grid sizing)
@@ -175,7 +178,10 @@ bool attn_uses_mfma(const AttnArgs& a);
 // Decode attention with a shared prefix: rollout rows r = g * G + i, one new query row
 // each; rows of a group share the group's first shared_pages[g] pages.
 struct DecodeAttnArgs {
-    AttnArgs base;               // seqs = per-rollout descriptors (n_rows = 1)
+    AttnArgs base;               // seqs = per-rollout descriptors (n_rows = 1); base.rows = query rows
+    int n_rollouts;              // rollout rows r = g * G + i covered (= base.rows unless compacted)
+    const int32_t* row_of = nullptr;  // compacted batch: rollout -> query / output row, < 0 = finished
+                                      // (base.row_seq is then the inverse map); NULL: row = rollout
     int G;
     const int32_t* shared_pages;  // per group: full prefix pages shared by its rollouts
     int max_shared_pages;
@@ -230,6 +236,11 @@ hipError_t launch_objective(const float* lp_new, const float* lp_old, const floa
                             double* per_rollout, float* j_out, hipStream_t s);
 hipError_t launch_shape_rewards(const float* rewards, const int32_t* lengths, int n_groups, int G, float alpha,
                                 float lo, float hi, float* out, hipStream_t s);
+// Compaction of a decode batch: live[c] = c-th rollout row r < n_rows with active[r] != 0 (in
+// increasing r; -1 for c >= their number), row_of[r] = c or -1, and their number to *count_dev
+// and, if given, as (generation << 32 | number) to *mailbox (device address of mapped host memory).
+hipError_t launch_compact_rows(const uint8_t* active, int n_rows, int32_t* live, int32_t* row_of,
+                               int32_t* count_dev, uint64_t* mailbox, uint32_t generation, hipStream_t s);
 hipError_t launch_advantages(const float* rewards, int n_groups, int G, int ddof, float eps, float* adv,
                              hipStream_t s);
 

@@ -186,7 +186,7 @@ bool make_dims(const rpo_model* m, int n_groups, int G, int max_prefix, int max_
 // Workspace carve-up (byte offsets, each 256-aligned).
 struct WsLayout {
     size_t x, h, qkv, attn, gu, act, hl, logits, blkmax, partial, rope, tables, group_desc, rollout_desc,
-        chunk_desc, row_seq, tok_index, lm_idx, shared_pages, fork_src, fork_dst, last_idx, total;
+        chunk_desc, row_seq, tok_index, lm_idx, shared_pages, fork_src, fork_dst, last_idx, live, row_of, count, total;
 };
 
 WsLayout make_layout(const rpo_model* m, const BatchDims& bd) {
@@ -222,6 +222,9 @@ WsLayout make_layout(const rpo_model* m, const BatchDims& bd) {
     L.fork_src = take((size_t)bd.B * 4);
     L.fork_dst = take((size_t)bd.B * 4);
     L.last_idx = take((size_t)bd.n_groups * 4);
+    L.live = take((size_t)bd.B * 4);     // compacted decode: query row -> rollout
+    L.row_of = take((size_t)bd.B * 4);   //                   rollout -> query row
+    L.count = take(4);
     L.total = off;
     return L;
 }
@@ -240,6 +243,16 @@ struct rpo_batch {
     int state;
     int step;
     std::vector<int> prefix_len;  // S_g
+    // Compacted decode: the compaction kernel reports (generation << 32 | live rows) into this
+    // pinned host word; the host sizes the next launches from the latest report of the current
+    // generation (the number of live rows never grows inside a rollout, so a late report is
+    // still an upper bound).  A new generation starts at every fork.
+    volatile uint64_t* mailbox = nullptr;   // host address (hipHostMalloc)
+    uint64_t* mailbox_dev = nullptr;        // the same word as the device sees it
+    uint32_t generation = 0;
+    ~rpo_batch() {
+        if (mailbox) (void)hipHostFree((void*)mailbox);
+    }
     // host staging that must outlive the enqueue of its copy
     std::vector<std::vector<int32_t>> stage_i32;
     std::vector<std::vector<SeqDesc>> stage_desc;
@@ -346,6 +359,20 @@ extern "C" int rpo_batch_create(const rpo_model* m, int32_t n_groups, int32_t G,
     b->geom.page_tokens = page_tokens;
     b->geom.n_pages = bd.n_pages;
     hipStream_t s = (hipStream_t)stream;
+    {
+        void* host = nullptr;
+        void* dev = nullptr;
+        hipError_t em = hipHostMalloc(&host, 64, hipHostMallocDefault);
+        if (em == hipSuccess) em = hipHostGetDevicePointer(&dev, host, 0);
+        if (em != hipSuccess) {
+            if (host) (void)hipHostFree(host);
+            delete b;
+            return fail(RPO_EHIP, "rpo_batch_create: pinned mailbox: %s", hipGetErrorString(em));
+        }
+        b->mailbox = (volatile uint64_t*)host;
+        b->mailbox_dev = (uint64_t*)dev;
+        *b->mailbox = 0;
+    }
 
     // Rotary table in fp64 on the host: angle = pos * base^(-2 i / dh).
     const int half = m->d.head_dim / 2;
@@ -395,6 +422,10 @@ struct PassCfg {
     double attn_flops = 0.0;  // algorithmic work of ONE layer's attention launch (for timing reports)
     double attn_bytes = 0.0;
     void* final_norm_out = nullptr;  // if set: final RMSNorm of all rows is written here by the last layer
+    // compacted decode step: rows are query rows, row_seq maps them to rollouts (< 0: padding),
+    // row_of is the inverse map, n_rollouts the rollout rows covered
+    const int32_t* row_of = nullptr;
+    int n_rollouts = 0;
 };
 
 #define RET_IF(expr)                       \
@@ -491,6 +522,7 @@ hipError_t run_layers(rpo_batch* b, const PassCfg& pc, hipStream_t s) {
         ra.row_seq = pc.row_seq;
         ra.seqs = pc.seqs;
         ra.pos_add = pc.pos_add;
+        ra.single_row = pc.row_of ? 1 : 0;
         ra.tables = b->at<int32_t>(L.tables);
         ra.active = pc.active;
         ra.kv_pool = b->kv;
@@ -513,6 +545,7 @@ hipError_t run_layers(rpo_batch* b, const PassCfg& pc, hipStream_t s) {
         aa.n_seqs = pc.n_seqs;
         aa.max_seq_rows = pc.max_seq_rows;
         aa.pos_add = pc.pos_add;
+        aa.single_row = pc.row_of ? 1 : 0;
         aa.tables = b->at<int32_t>(L.tables);
         aa.active = pc.active;
         aa.kv_pool = b->kv;
@@ -523,6 +556,8 @@ hipError_t run_layers(rpo_batch* b, const PassCfg& pc, hipStream_t s) {
         if (pc.decode) {
             DecodeAttnArgs da;
             da.base = aa;
+            da.n_rollouts = pc.row_of ? pc.n_rollouts : pc.rows;
+            da.row_of = pc.row_of;
             da.G = b->bd.G;
             da.shared_pages = b->at<int32_t>(L.shared_pages);
             da.max_shared_pages = pc.max_shared_pages;
@@ -712,42 +747,43 @@ extern "C" int rpo_kv_fork(rpo_batch* b, void* stream) {
                              b->at<int32_t>(L.fork_dst), bd.B, s));
     b->state = kForked;
     b->step = 0;
+    b->generation += 1;
+    *b->mailbox = ((uint64_t)b->generation << 32) | (uint32_t)bd.B;
     return RPO_OK;
 }
 
 // ---------------------------------------------------------------------------
-extern "C" int rpo_decode_step(rpo_batch* b, const int32_t* tokens_dev, int32_t n_rows,
-                               const uint8_t* active_dev, float* logits_dev, float* row_max_out_dev,
-                               void* stream) {
-    if (!b || !tokens_dev || !logits_dev) return fail(RPO_EINVAL, "rpo_decode_step: NULL argument");
-    if (b->state != kForked) return fail(RPO_ESTATE, "rpo_decode_step: call rpo_kv_fork first");
+namespace {
+// One decode step on `rows` query rows.  Plain: query row = rollout row, rows = n_rollouts.
+// Compacted: query row c belongs to rollout live[c] (padding rows: -1), row_of is the inverse map.
+int decode_step_body(rpo_batch* b, const int32_t* tokens_dev, int rows, int n_rollouts, const uint8_t* active_dev,
+                     const int32_t* live, const int32_t* row_of, float* logits_dev, float* row_max_out_dev,
+                     hipStream_t s) {
     const BatchDims& bd = b->bd;
-    if (n_rows < 1 || n_rows > bd.B) return fail(RPO_EINVAL, "rpo_decode_step: n_rows %d not in 1..%d", n_rows, bd.B);
-    if (b->step >= bd.max_suffix)
-        return fail(RPO_ESTATE, "rpo_decode_step: step %d would exceed max_suffix %d", b->step, bd.max_suffix);
-    hipStream_t s = (hipStream_t)stream;
     const rpo_model_desc& d = b->m->d;
     const WsLayout& L = b->L;
-    HIP_TRY(launch_embed(tokens_dev, nullptr, b->m->embed, d.dtype, d.vocab, d.d_model, b->at<float>(L.x),
-                         n_rows, s));
+    HIP_TRY(launch_embed(tokens_dev, live, b->m->embed, d.dtype, d.vocab, d.d_model, b->at<float>(L.x), rows, s));
     int max_shared = 0;
-    for (int g = 0; g < ceil_div(n_rows, bd.G); ++g) max_shared = std::max(max_shared, b->prefix_len[g] / bd.pt);
+    for (int g = 0; g < ceil_div(n_rollouts, bd.G); ++g) max_shared = std::max(max_shared, b->prefix_len[g] / bd.pt);
     PassCfg pc;
-    pc.rows = n_rows;
-    pc.row_seq = nullptr;
+    pc.rows = rows;
+    pc.row_seq = live;
     pc.seqs = b->at<SeqDesc>(L.rollout_desc);
-    pc.n_seqs = n_rows;
+    pc.n_seqs = n_rollouts;
     pc.max_seq_rows = 1;
     pc.pos_add = b->step;
-    pc.active = active_dev;
+    pc.active = live ? nullptr : active_dev;
     pc.decode = true;
     pc.max_shared_pages = max_shared;
+    pc.row_of = row_of;
+    pc.n_rollouts = n_rollouts;
     {
         // Algorithmic work of one layer's decode attention: the shared prefix pages of every live
-        // group are read ONCE per group, each rollout's private tokens once per rollout.
+        // group are read ONCE per group, each rollout's private tokens once per rollout (a
+        // compacted step is priced as if every covered rollout were live).
         const double tok_bytes = 2.0 * d.n_kv_heads * d.head_dim * dtype_size(d.dtype);
         double toks = 0.0, qk = 0.0;
-        for (int r = 0; r < n_rows; ++r) {
+        for (int r = 0; r < n_rollouts; ++r) {
             const int g = r / bd.G;
             const int ctx = b->prefix_len[g] + b->step + 1;
             const int shared_tok = (b->prefix_len[g] / bd.pt) * bd.pt;
@@ -761,11 +797,11 @@ extern "C" int rpo_decode_step(rpo_batch* b, const int32_t* tokens_dev, int32_t 
     pc.final_norm_out = b->at<void>(L.hl);
     HIP_TRY(run_layers(b, pc, s));
     if (!row_max_out_dev) {
-        HIP_TRY(gemm(b, b->at<void>(L.hl), d.d_model, b->m->lm_head, d.d_model, logits_dev, d.vocab, n_rows, d.vocab,
+        HIP_TRY(gemm(b, b->at<void>(L.hl), d.d_model, b->m->lm_head, d.d_model, logits_dev, d.vocab, rows, d.vocab,
                      d.d_model, kEpiStoreF32, s));
     } else {
         // the LM-head epilogue leaves each row's maximum per column block where it can
-        GemmArgs g = gemm_args(b, b->at<void>(L.hl), d.d_model, b->m->lm_head, d.d_model, logits_dev, d.vocab, n_rows,
+        GemmArgs g = gemm_args(b, b->at<void>(L.hl), d.d_model, b->m->lm_head, d.d_model, logits_dev, d.vocab, rows,
                                d.vocab, d.d_model, kEpiStoreF32);
         LseFuse bm;
         bm.part = b->at<float>(L.blkmax);
@@ -778,16 +814,58 @@ extern "C" int rpo_decode_step(rpo_batch* b, const int32_t* tokens_dev, int32_t 
         }
         const bool fused = gemm_fuses_max(g) > 0;
         const double es = (double)dtype_size(g.dtype);
-        HIP_TRY(timed(gemm_kernel_id(g), 2.0 * n_rows * (double)d.vocab * d.d_model,
-                      ((double)n_rows * d.d_model + (double)d.vocab * d.d_model) * es + (double)n_rows * d.vocab * 4.0,
+        HIP_TRY(timed(gemm_kernel_id(g), 2.0 * rows * (double)d.vocab * d.d_model,
+                      ((double)rows * d.d_model + (double)d.vocab * d.d_model) * es + (double)rows * d.vocab * 4.0,
                       s, [&] { return launch_gemm(g, s); }));
         if (fused)
-            HIP_TRY(launch_row_max_blocks(bm.part, bm.blocks, row_max_out_dev, n_rows, s));
+            HIP_TRY(launch_row_max_blocks(bm.part, bm.blocks, row_max_out_dev, rows, s));
         else
-            HIP_TRY(launch_row_max(logits_dev, d.vocab, d.vocab, row_max_out_dev, n_rows, s));
+            HIP_TRY(launch_row_max(logits_dev, d.vocab, d.vocab, row_max_out_dev, rows, s));
     }
     b->step += 1;
     return RPO_OK;
+}
+}  // namespace
+
+extern "C" int rpo_decode_step(rpo_batch* b, const int32_t* tokens_dev, int32_t n_rows,
+                               const uint8_t* active_dev, float* logits_dev, float* row_max_out_dev,
+                               void* stream) {
+    if (!b || !tokens_dev || !logits_dev) return fail(RPO_EINVAL, "rpo_decode_step: NULL argument");
+    if (b->state != kForked) return fail(RPO_ESTATE, "rpo_decode_step: call rpo_kv_fork first");
+    const BatchDims& bd = b->bd;
+    if (n_rows < 1 || n_rows > bd.B) return fail(RPO_EINVAL, "rpo_decode_step: n_rows %d not in 1..%d", n_rows, bd.B);
+    if (b->step >= bd.max_suffix)
+        return fail(RPO_ESTATE, "rpo_decode_step: step %d would exceed max_suffix %d", b->step, bd.max_suffix);
+    return decode_step_body(b, tokens_dev, n_rows, n_rows, active_dev, nullptr, nullptr, logits_dev, row_max_out_dev,
+                            (hipStream_t)stream);
+}
+
+extern "C" int rpo_decode_step_compact(rpo_batch* b, const int32_t* tokens_dev, int32_t n_rows,
+                                       const uint8_t* active_dev, float* logits_dev, float* row_max_out_dev,
+                                       int32_t* row_of_out_dev, int32_t* n_logit_rows_out, void* stream) {
+    if (!b || !tokens_dev || !logits_dev || !active_dev || !row_of_out_dev || !n_logit_rows_out)
+        return fail(RPO_EINVAL, "rpo_decode_step_compact: NULL argument");
+    if (b->state != kForked) return fail(RPO_ESTATE, "rpo_decode_step_compact: call rpo_kv_fork first");
+    const BatchDims& bd = b->bd;
+    if (n_rows < 1 || n_rows > bd.B)
+        return fail(RPO_EINVAL, "rpo_decode_step_compact: n_rows %d not in 1..%d", n_rows, bd.B);
+    if (b->step >= bd.max_suffix)
+        return fail(RPO_ESTATE, "rpo_decode_step_compact: step %d would exceed max_suffix %d", b->step, bd.max_suffix);
+    hipStream_t s = (hipStream_t)stream;
+    const WsLayout& L = b->L;
+    // latest report of this rollout's compaction kernel: an upper bound of the rows still live
+    const uint64_t report = *b->mailbox;
+    int rows = n_rows;
+    if ((uint32_t)(report >> 32) == b->generation) rows = std::min(rows, (int)(uint32_t)report);
+    HIP_TRY(launch_compact_rows(active_dev, n_rows, b->at<int32_t>(L.live), row_of_out_dev, b->at<int32_t>(L.count),
+                                b->mailbox_dev, b->generation, s));
+    *n_logit_rows_out = rows;
+    if (rows == 0) {  // every rollout has finished: nothing to compute, the step still counts
+        b->step += 1;
+        return RPO_OK;
+    }
+    return decode_step_body(b, tokens_dev, rows, n_rows, active_dev, b->at<int32_t>(L.live), row_of_out_dev,
+                            logits_dev, row_max_out_dev, s);
 }
 
 // ---------------------------------------------------------------------------
@@ -828,6 +906,7 @@ extern "C" int rpo_attn_decode(rpo_batch* b, int32_t layer, const void* q_dev, i
     aa.path = g_kernel_path;
     DecodeAttnArgs da;
     da.base = aa;
+    da.n_rollouts = n_rows;
     da.G = bd.G;
     da.shared_pages = b->at<int32_t>(L.shared_pages);
     int max_shared = 0;

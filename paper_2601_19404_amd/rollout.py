@@ -31,6 +31,9 @@ def order_by_suffix_length(m):
     return np.argsort(-np.asarray(m), kind="stable")
 
 
+COMPACT_LAG = 8   # decode steps the host may run ahead of the device in a compacted rollout
+
+
 @dataclass
 class RolloutResult:
     tokens: torch.Tensor          # int32 [B, max_m] sampled suffix tokens (row r = group * G + i)
@@ -40,11 +43,14 @@ class RolloutResult:
     n_generated: int
     logits: list | None = None    # per step: fp32 [rows, V] copies when keep_logits
     lengths: torch.Tensor | None = None   # int32 [B] tokens generated per rollout (with eos_id)
+    row_of: list | None = None    # compacted rollouts: per decode step, int32 [rows] rollout -> logits row
+    rows_computed: list | None = None     # compacted rollouts: logits rows each decode step computed
 
 
 def suffix_rollout(batch: rpo.Batch, prompts, cached, m, temperature: float, seed: int,
                    seq_ids: torch.Tensor, keep_logits: bool | int = False, stream=None,
-                   marks: list | None = None, eos_id: int | None = None, prefix=None) -> RolloutResult:
+                   marks: list | None = None, eos_id: int | None = None, prefix=None,
+                   compact: bool = False) -> RolloutResult:
     """Regenerate m_k tokens for each of the G rollouts of every group.
 
     Groups must be ordered by decreasing m (see order_by_suffix_length) so that the
@@ -55,7 +61,10 @@ def suffix_rollout(batch: rpo.Batch, prompts, cached, m, temperature: float, see
     eos_id: if given, a rollout that samples it stops there (its later tokens are eos_id padding,
     it appends no more K/V) and the per-rollout lengths are returned; m is then the cap.
     prefix: (packed prefix tokens on the device, cu_len host array) when the cut was already made
-    on the device (DeviceCachePool.cut_pack); prompts / cached are then not read."""
+    on the device (DeviceCachePool.cut_pack); prompts / cached are then not read.
+    compact (with eos_id): finished rollouts leave the decode batch (rpo_decode_step_compact) instead
+    of being masked; kept logits are then in compacted row order, RolloutResult.row_of says which
+    row of step j belongs to which rollout, RolloutResult.rows_computed how many rows each step ran."""
     cfg = batch.model.cfg
     G, ng = batch.G, batch.n_groups
     B = ng * G
@@ -71,7 +80,8 @@ def suffix_rollout(batch: rpo.Batch, prompts, cached, m, temperature: float, see
     max_m = int(m.max()) if ng else 0
     last_logits = torch.empty((ng, V), dtype=torch.float32, device="cuda")
     logits = torch.empty((B, V), dtype=torch.float32, device="cuda")
-    out_tokens = torch.zeros((max_m, B), dtype=torch.int32, device="cuda")
+    # positions a rollout never reaches hold the end-of-sequence id when there is one, else 0
+    out_tokens = torch.full((max_m, B), 0 if eos_id is None else int(eos_id), dtype=torch.int32, device="cuda")
     out_lp = torch.zeros((max_m, B), dtype=torch.float32, device="cuda")
     row_map = torch.arange(B, dtype=torch.int32, device="cuda") // G
     row_max = torch.empty(B, dtype=torch.float32, device="cuda")   # per-row logits maximum from the LM head
@@ -83,6 +93,11 @@ def suffix_rollout(batch: rpo.Batch, prompts, cached, m, temperature: float, see
         lengths = torch.zeros(B, dtype=torch.int32, device="cuda")
     kept = [] if keep_logits else None
     n_keep = max_m if keep_logits is True else int(keep_logits)
+    if compact and eos_id is None:
+        raise ValueError("compact=True needs an end-of-sequence id")
+    row_of = torch.empty(B, dtype=torch.int32, device="cuda") if compact else None
+    kept_row_of, rows_computed = ([], []) if compact else (None, None)
+    step_done = []
 
     import time
 
@@ -108,6 +123,25 @@ def suffix_rollout(batch: rpo.Batch, prompts, cached, m, temperature: float, see
         n = live_groups[j] * G
         if n == 0:
             break
+        if compact:
+            # the host learns the live-row count from the device without waiting; letting it run at
+            # most LAG steps ahead keeps that report fresh
+            if len(step_done) >= COMPACT_LAG:
+                step_done[-COMPACT_LAG].synchronize()
+            n_logit = rpo.rpo_decode_step_compact(batch, out_tokens[j - 1], n, active, logits, row_of, stream,
+                                                  row_max)
+            rows_computed.append(n_logit)
+            if n_logit == 0:
+                break
+            rpo.rpo_sample(logits, n_logit, V, V, row_of, n, temperature, seed, seq_ids, j, out_tokens[j],
+                           out_lp[j], stream, eos, active, lengths, row_max)
+            ev = torch.cuda.Event()
+            ev.record(stream)
+            step_done.append(ev)
+            if j < n_keep:
+                kept.append(logits[:n_logit].clone())
+                kept_row_of.append(row_of[:n].clone())
+            continue
         rpo.rpo_decode_step(batch, out_tokens[j - 1], n, active, logits, stream, row_max)
         rpo.rpo_sample(logits, n, V, V, None, n, temperature, seed, seq_ids, j, out_tokens[j],
                        out_lp[j], stream, eos, active, lengths, row_max)
@@ -115,7 +149,7 @@ def suffix_rollout(batch: rpo.Batch, prompts, cached, m, temperature: float, see
             kept.append(logits[:n].clone())
     mark("decode")
     return RolloutResult(out_tokens.t().contiguous(), out_lp.t().contiguous(), m, cu,
-                         int(m.sum()) * G, kept, lengths)
+                         int(m.sum()) * G, kept, lengths, kept_row_of, rows_computed)
 
 
 def suffix_index(m, G: int, max_m: int):

@@ -52,14 +52,15 @@ def rpo():
 
 def run_case(rpo, mcfg, prompts, cached, m, G, temperature=1.0, seed=3, page=64, path=0,
              max_rows=None, weight_seed=1234, perturb=True, check_logprobs=True, n_layers=None,
-             eos_from=None, oracle_rollouts=None):
+             eos_from=None, oracle_rollouts=None, compact=False):
     """One batch through librpo, then element-by-element against the oracle.
 
     eos_from = (row, step): a first, unconstrained run picks the token that rollout `row` drew at
     `step`; the checked run then uses it as the end-of-sequence id, so that rollout (and any other
     that happens to draw the id) stops early and the `active` mask reaches every decode kernel.
     oracle_rollouts: which rollouts of each group the oracle recomputes (default: all G); the
-    integer contract (oracle sampler on the GPU's logits) always covers every row and step."""
+    integer contract (oracle sampler on the GPU's logits) always covers every row and step.
+    compact: the checked run drops finished rollouts from the decode batch (rpo_decode_step_compact)."""
     from paper_2601_19404_amd import rollout
     rpo.rpo_set_kernel_path(path)
     w = synth.make_weights(mcfg, seed=weight_seed, n_layers=n_layers)
@@ -88,11 +89,19 @@ def run_case(rpo, mcfg, prompts, cached, m, G, temperature=1.0, seed=3, page=64,
         torch.cuda.synchronize()
         eos = int(free.tokens[eos_from[0], eos_from[1]].item())
     res = rollout.suffix_rollout(batch, prompts, cached, m, temperature, seed, seq_ids, keep_logits=True,
-                                 eos_id=eos)
+                                 eos_id=eos, compact=compact)
     torch.cuda.synchronize()
     toks = res.tokens.cpu().numpy()
     slp = res.sample_logprobs.cpu().numpy()
     kept = [k.cpu().numpy() for k in res.logits]
+    row_of = [None] + [t.cpu().numpy() for t in res.row_of] if compact else None
+
+    def logits_row(j, r):
+        """The logits row rollout r drew its token j from."""
+        if j == 0:
+            return kept[0][r // G]
+        return kept[j][row_of[j][r] if compact else r]
+
     sid = np.arange(1000, 1000 + B).astype(np.uint64)
     tol = TOL[mcfg.dtype]
     # tokens each rollout really generated (the end-of-sequence token counts)
@@ -118,8 +127,20 @@ def run_case(rpo, mcfg, prompts, cached, m, G, temperature=1.0, seed=3, page=64,
         if n == 0:
             break
         live = np.flatnonzero(n_gen[:n] > j)
-        z = kept[0][live // G] if j == 0 else kept[j][live]
+        if len(live) == 0:
+            continue
+        z = np.stack([logits_row(j, r) for r in live])
         util.check_sampler_consistency(z, temperature, seed, sid[live], j, toks[live, j])
+    if compact:
+        # finished rollouts really left the batch: at some step fewer rows ran than rollouts were covered
+        covered = [int(np.sum(m > j)) * G for j in range(1, 1 + len(res.rows_computed))]
+        assert all(c <= n for c, n in zip(res.rows_computed, covered))
+        assert any(c < n for c, n in zip(res.rows_computed, covered)), "no step ran on fewer rows"
+        for j in range(1, len(row_of)):
+            n = covered[j - 1]
+            alive = n_gen[:n] > j
+            assert np.all(row_of[j][:n][~alive] == -1)
+            np.testing.assert_array_equal(row_of[j][:n][alive], np.arange(int(alive.sum())))
 
     # (a) floating point: oracle logits teacher-forced on the GPU's tokens
     which = range(G) if oracle_rollouts is None else oracle_rollouts
@@ -134,7 +155,7 @@ def run_case(rpo, mcfg, prompts, cached, m, G, temperature=1.0, seed=3, page=64,
             if mg == 0:
                 continue
             ref = T.teacher_forced_logits(shape, w_np, prefix, toks[r, :mg])
-            got = np.stack([kept[j][g if j == 0 else r] for j in range(mg)]).astype(np.float64)
+            got = np.stack([logits_row(j, r) for j in range(mg)]).astype(np.float64)
             if shape_q.storage != "f64" and i == which[0]:
                 ref_q = T.teacher_forced_logits(shape_q, w_np, prefix, toks[r, :mg])
                 floor.append((ref_q - ref).ravel())
@@ -294,6 +315,17 @@ def test_bf16_long_suffix_with_end_of_sequence(rpo):
     epilogue and the sampler on the MFMA path; live rows against the oracle, stopped rows padded."""
     p, a, m = long_suffix_workload(BF16_SMALL, 24, lens=(500, 450, 380), ms=(180, 160, 140), seed=32)
     run_case(rpo, BF16_SMALL, p, a, m, G=8, temperature=0.7, eos_from=(9, 70), oracle_rollouts=(0, 1, 5))
+
+
+@pytest.mark.parametrize("mcfg,page", [(BF16_SMALL, 64), (synth.TINY, 16)])
+def test_end_of_sequence_with_batch_compaction(rpo, mcfg, page):
+    """Variable-length rollouts with finished rollouts REMOVED from the decode batch
+    (rpo_decode_step_compact): the rows of a step are the live rollouts in order, the projections
+    run on them only, and every live row still matches the oracle (MFMA kernels and, on the fp32
+    model, the generic ones)."""
+    p, a, m = long_suffix_workload(mcfg, 24, lens=(200, 170, 140), ms=(90, 80, 70), seed=35)
+    run_case(rpo, mcfg, p, a, m, G=8, temperature=0.7, page=page, eos_from=(9, 20), oracle_rollouts=(0, 1, 5),
+             compact=True)
 
 
 def test_bf16_prompt_only_prefix_decoded_past_two_pages(rpo):
