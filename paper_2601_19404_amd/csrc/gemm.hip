@@ -19,8 +19,6 @@
 //    multiple of 64 (and selectable for comparison).
 //  * gemm_generic_kernel: any dtype on the vector ALUs (fp32 tiny model, shapes the
 //    MFMA kernels do not take).
-#include <stdlib.h>
-
 #include "kernels.hpp"
 
 namespace rpo {
@@ -1131,11 +1129,11 @@ hipError_t launch_one(const GemmArgs& a, int splits, void* out, hipStream_t s) {
 }
 
 template <int BM, int BN, int WM, int WN, int DST = kDmaStages, int DBK = kDmaBK>
-hipError_t launch_tile(const GemmArgs& a, int splits, hipStream_t s, bool via_ws = false) {
+hipError_t launch_tile(const GemmArgs& a, int splits, hipStream_t s) {
     const bool sw = a.epilogue == kEpiSwiglu;
     constexpr bool kPairs = (BN / WN / 32) % 2 == 0;  // a wave holds gate/up block pairs
     if (sw && !kPairs) return hipErrorInvalidValue;
-    if (splits > 1 || via_ws) {
+    if (splits > 1) {
         hipError_t e;
         if constexpr (kPairs) {
             e = sw ? launch_one<BM, BN, WM, WN, kEpiPartial, true, DST, DBK>(a, splits, a.ws, s)
@@ -1247,15 +1245,6 @@ int gemm_kernel_id(const GemmArgs& a) {
     return (id == kKidGemm256 && a.epilogue == kEpiSwiglu) ? (int)kKidGemm256Swiglu : id;
 }
 
-// The output projection of a decode step (64x64 tiles, no K split) followed by an RMSNorm: the
-// tiles write their fp32 result to the workspace and the reduction kernel adds the residual and
-// normalises, instead of a read-modify-write epilogue followed by a stand-alone RMSNorm launch.
-static bool norm_via_workspace(const GemmArgs& a, const TileCfg& t) {
-    static const bool on = getenv("RPO_EXP_NORM_WS") != nullptr;
-    return on && t.id == kKidGemm64x64 && a.epilogue == kEpiAddF32 && a.norm_out && norm_fusable(a) && a.ws &&
-           (size_t)a.M * a.N * sizeof(float) <= a.ws_bytes && a.K % kBK == 0 && a.path != 2;
-}
-
 static hipError_t launch_gemm_only(const GemmArgs& a, int splits, const TileCfg& t, hipStream_t s) {
     switch (t.id) {
         case kKidGemm256:
@@ -1271,7 +1260,7 @@ static hipError_t launch_gemm_only(const GemmArgs& a, int splits, const TileCfg&
             }
             return launch_tile<32, 128, 1, 4, 4>(a, splits, s);
         case kKidGemm64x64:
-            return launch_tile<64, 64, 2, 2, 4>(a, splits, s, norm_via_workspace(a, t));
+            return launch_tile<64, 64, 2, 2, 4>(a, splits, s);
         case kKidGemm256x160:
             return launch_one<256, 160, 4, 1, kEpiSwiglu, 2>(a, 1, a.C, s);
         case kKidGemm256x192:
@@ -1305,7 +1294,7 @@ hipError_t launch_gemm(const GemmArgs& a, hipStream_t s) {
             return launch_one<256, 256, 2, 4, kEpiLogitsMax, false>(a, 1, a.C, s);
         }
         e = launch_gemm_only(a, splits, t, s);
-        norm_done = want_norm && (splits > 1 || norm_via_workspace(a, t)) && norm_fusable(a);  // fused into the reduction
+        norm_done = want_norm && splits > 1 && norm_fusable(a);  // fused into the K-split reduction
         rope_done = (splits > 1 && rope_fusable(a)) || (t.id == kKidGemm32 && rope_direct(a));
     }
     if (e != hipSuccess) return e;
