@@ -105,8 +105,14 @@ static hipError_t launch_attn_generic(const AttnArgs& a, hipStream_t s) {
 // ---------------------------------------------------------------------------
 constexpr int kDh = 128;      // head_dim of the MFMA kernels
 constexpr int kPt = 64;       // tokens per page
-constexpr int kKRow = kDh + 8;  // LDS row of the K tile  [64][136]
-constexpr int kVRow = kPt + 8;  // LDS row of the V^T tile [128][72]
+// LDS tiles are unpadded; bank conflicts of the fragment reads are avoided by permuting the 16-byte
+// pieces of a row with the row index.  K tile [64 tokens][128 channels]: piece p of row r sits at
+// p ^ (r & 7), so the 16-byte reads of eight consecutive rows (same piece) cover all 32 banks.
+// V^T tile [128 channels][64 tokens]: piece p (eight tokens) of row r sits at p ^ (r & 7) with its
+// two 8-byte halves exchanged when r & 8, so the 8-byte reads of sixteen consecutive rows (same
+// tokens) cover all 32 banks too.
+constexpr int kKRow = kDh;  // LDS row of the K tile  [64][128]
+constexpr int kVRow = kPt;  // LDS row of the V^T tile [128][64]
 constexpr int kKTile = kPt * kKRow;
 constexpr int kVTile = kDh * kVRow;
 constexpr size_t kAttnLds = (size_t)2 * (kKTile + kVTile) * sizeof(bf16);
@@ -178,9 +184,12 @@ __device__ inline void attn_stream_pages(const bf16* const (&qptr)[NC], const in
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int c = tid + i * 256;
-            *(u32x4_t*)(Ks + buf * kKTile + (c >> 4) * kKRow + (c & 15) * 8) = rk[i];
+            const int kr = c >> 4;
+            *(u32x4_t*)(Ks + buf * kKTile + kr * kKRow + (((c & 15) ^ (kr & 7)) << 3)) = rk[i];
             // V block piece c = (token group c / 128, channel c % 128) -> LDS row = channel
-            *(u32x4_t*)(Vs + buf * kVTile + (c & (kDh - 1)) * kVRow + (c >> 7) * 8) = rv[i];
+            const int vr = c & (kDh - 1);
+            const u32x4_t v = (vr & 8) ? u32x4_t{rv[i].z, rv[i].w, rv[i].x, rv[i].y} : rv[i];
+            *(u32x4_t*)(Vs + buf * kVTile + vr * kVRow + ((((c >> 7)) ^ (vr & 7)) << 3)) = v;
         }
     };
 
@@ -201,7 +210,7 @@ __device__ inline void attn_stream_pages(const bf16* const (&qptr)[NC], const in
                 for (int c = 0; c < NC; ++c) sc[c][mb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int kk = 0; kk < 4; ++kk) {
-                    const bf16x8_t ak = *(const bf16x8_t*)(ks + (mb * 16 + c16) * kKRow + kk * 32 + 8 * g);
+                    const bf16x8_t ak = *(const bf16x8_t*)(ks + (mb * 16 + c16) * kKRow + (((kk * 4 + g) ^ (c16 & 7)) << 3));
 #pragma unroll
                     for (int c = 0; c < NC; ++c)
                         sc[c][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ak, bq[c][kk], sc[c][mb], 0, 0, 0);
@@ -264,9 +273,11 @@ __device__ inline void attn_stream_pages(const bf16* const (&qptr)[NC], const in
             for (int kk2 = 0; kk2 < 2; ++kk2) {
 #pragma unroll
                 for (int mb2 = 0; mb2 < 8; ++mb2) {
-                    const bf16* vp = vs + (mb2 * 16 + c16) * kVRow + 32 * kk2 + 4 * g;
-                    const bf16x4_t lo = *(const bf16x4_t*)vp;
-                    const bf16x4_t hi = *(const bf16x4_t*)(vp + 16);
+                    // tokens 32 kk2 + 4 g .. + 3 = half (g & 1) of piece 4 kk2 + g / 2; "hi" is two pieces on
+                    const bf16* vrow = vs + (mb2 * 16 + c16) * kVRow + (((g & 1) ^ (c16 >> 3)) << 2);
+                    const int vp0 = 4 * kk2 + (g >> 1);
+                    const bf16x4_t lo = *(const bf16x4_t*)(vrow + ((vp0 ^ (c16 & 7)) << 3));
+                    const bf16x4_t hi = *(const bf16x4_t*)(vrow + (((vp0 + 2) ^ (c16 & 7)) << 3));
                     const bf16x8_t av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 #pragma unroll
                     for (int c = 0; c < NC; ++c)
