@@ -107,7 +107,8 @@ constexpr int kDh = 128;      // head_dim of the MFMA kernels
 constexpr int kPt = 64;       // tokens per page
 // LDS tiles are unpadded; bank conflicts of the fragment reads are avoided by permuting the 16-byte
 // pieces of a row with the row index.  K tile [64 tokens][128 channels]: piece p of row r sits at
-// p ^ (r & 7), so the 16-byte reads of eight consecutive rows (same piece) cover all 32 banks.
+// p ^ (r & 15), so the 16-byte reads of sixteen consecutive rows (same piece) are spread evenly
+// over the banks whichever lanes the LDS serves together.
 // V^T tile [128 channels][64 tokens]: piece p (eight tokens) of row r sits at p ^ (r & 7) with its
 // two 8-byte halves exchanged when r & 8, so the 8-byte reads of sixteen consecutive rows (same
 // tokens) cover all 32 banks too.
@@ -185,7 +186,7 @@ __device__ inline void attn_stream_pages(const bf16* const (&qptr)[NC], const in
         for (int i = 0; i < 4; ++i) {
             const int c = tid + i * 256;
             const int kr = c >> 4;
-            *(u32x4_t*)(Ks + buf * kKTile + kr * kKRow + (((c & 15) ^ (kr & 7)) << 3)) = rk[i];
+            *(u32x4_t*)(Ks + buf * kKTile + kr * kKRow + (((c & 15) ^ (kr & 15)) << 3)) = rk[i];
             // V block piece c = (token group c / 128, channel c % 128) -> LDS row = channel
             const int vr = c & (kDh - 1);
             const u32x4_t v = (vr & 8) ? u32x4_t{rv[i].z, rv[i].w, rv[i].x, rv[i].y} : rv[i];
@@ -210,7 +211,7 @@ __device__ inline void attn_stream_pages(const bf16* const (&qptr)[NC], const in
                 for (int c = 0; c < NC; ++c) sc[c][mb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int kk = 0; kk < 4; ++kk) {
-                    const bf16x8_t ak = *(const bf16x8_t*)(ks + (mb * 16 + c16) * kKRow + (((kk * 4 + g) ^ (c16 & 7)) << 3));
+                    const bf16x8_t ak = *(const bf16x8_t*)(ks + (mb * 16 + c16) * kKRow + (((kk * 4 + g) ^ c16) << 3));
 #pragma unroll
                     for (int c = 0; c < NC; ++c)
                         sc[c][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ak, bq[c][kk], sc[c][mb], 0, 0, 0);
