@@ -1,15 +1,21 @@
 // C[M,N] (op)= A[M,K] * W[N,K]^T with fp32 accumulation: the dense contractions of
 // the decoder (QKV, O, gate/up, down, LM head).  Both operands are K-contiguous.
 //
-//  * gemm_dma_kernel: bf16 operands on the CDNA4 matrix cores (v_mfma_f32_32x32x16_bf16).
-//    64-deep K slabs go from global memory straight into LDS (global_load_lds_dwordx4), two to
-//    four stages deep; fragments are double-buffered in registers.  Tile shapes and what they
-//    are for (pick_tile): 256x256 (many-tile problems: prefill / log-prob chunks, wide decode
-//    projections), 256x192 (large M with a narrow N), 128x128 and 64x128 (deep-K decode
-//    projections, split along K: the fp32 partial sums go to a workspace and a reduction kernel
-//    applies the epilogue -- deterministic, no floating-point atomics), 64x64 and 32x128
-//    (shallow-K decode projections, one tile per CU, no K split).  (tile, K-split) work items
-//    are dealt evenly to the 8 XCDs, neighbouring tiles to the same XCD (each has its own L2).
+//  * gemm_dma_kernel / gemm_dma2_kernel: bf16 operands on the CDNA4 matrix cores
+//    (v_mfma_f32_32x32x16_bf16).  64-deep K slabs go from global memory straight into LDS
+//    (global_load_lds_dwordx4), two to four stages deep; fragments are double-buffered in registers.
+//    Tile shapes and what they are for (pick_tile): 256x256 (many-tile problems: prefill / log-prob
+//    chunks, wide decode projections), 256x192 / 256x160 (large M with a narrow N, decode gate/up),
+//    128x128 and 64x128 (deep-K decode projections, split along K: the fp32 partial sums go to a
+//    workspace and a reduction kernel applies the epilogue -- deterministic, no floating-point
+//    atomics), 64x64 and 32x128 (shallow-K decode projections, one tile per CU, no K split).
+//    (tile, K-split) work items are dealt evenly to the 8 XCDs, neighbouring tiles to the same XCD
+//    (each has its own L2).  The wide two-stage tiles run on gemm_dma2_kernel: every MFMA is followed
+//    by one fragment read or one load (the matrix pipe never waits behind a burst of memory
+//    instructions), the barrier of a slab sits before its last k-step (the next slab's first
+//    fragments and the loads of the slab after it go out under that k-step's MFMAs), and when a
+//    launch has many rounds of tiles one resident workgroup per CU walks its share of them, the
+//    next tile's first loads in flight during the epilogue.
 //  * Epilogues ride on the accumulators: residual add, SwiGLU (the kernel reads the weight rows
 //    in the order [32 gate | 32 up | 32 gate | ...], so a wave holds matching gate and up
 //    columns), rotary embedding + KV page write (QKV projection of a decode step), log-sum-exp
@@ -334,12 +340,14 @@ struct TileCoord {
     int bm, bn, split;
     bool ok;
 };
-__device__ inline TileCoord tile_coord(int n_tiles, int splits, int grid_m, int grid_n) {
+// vb: the virtual block id to map (a workgroup that walks several tiles), or < 0: blockIdx.x.
+__device__ inline TileCoord tile_coord(int n_tiles, int splits, int grid_m, int grid_n, int vb = -1) {
     TileCoord t{0, 0, 0, false};
     const int total = n_tiles * splits;
-    const int xcd = blockIdx.x % kXcd;
+    const int bid = vb < 0 ? (int)blockIdx.x : vb;
+    const int xcd = bid % kXcd;
     const int start = (int)(((int64_t)xcd * total) / kXcd), next = (int)(((int64_t)(xcd + 1) * total) / kXcd);
-    const int item = start + blockIdx.x / kXcd;
+    const int item = start + bid / kXcd;
     if (item >= next) return t;
     t.split = item / n_tiles;
     int r = item % n_tiles;
@@ -549,6 +557,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const bf16* __res
     static_assert(BM % (ROWS_PER_INST * NW) == 0 && BN % (ROWS_PER_INST * NW) == 0, "tile/wave mismatch");
     static_assert(SWIGLU != 1 || NI % 2 == 0, "SwiGLU needs gate/up block pairs inside a wave");
     static_assert(STAGES >= 2 && STAGES <= 4, "pipeline depth");
+    static_assert(EPI != kEpiLse && EPI != kEpiLogitsMax, "these epilogues live on gemm_dma2_kernel");
     // Every epilogue but the rotary one and the plain bf16 store (measured: 2-byte stores of 32
     // neighbouring lanes beat 8-byte stores of 32 rows) multiplies with the operands swapped: the accumulators then
     // hold the transposed block, lane = row of A (l % 32), registers = 16 columns
@@ -667,73 +676,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const bf16* __res
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // drain the redundant tail loads before LDS is released
     }
 #undef RPO_DMA_SLAB
-    if constexpr (EPI == kEpiLse) {
-        const int half = lane >> 5;
-        const int blk = (n0 / BN) * WN + wn;
-        const int cbase = n0 + wn * TN;
-#pragma unroll
-        for (int i = 0; i < MI; ++i) {
-            const int r = m0 + wm * TM + i * 32 + (lane & 31);
-            const int tgt = r < M ? lf.target[r] : -1;
-            float mx = -INFINITY, zt = 0.f;
-            bool have = false;
-#pragma unroll
-            for (int j = 0; j < NI; ++j)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int col = cbase + j * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
-                    const float v = col < N ? acc[i][j][e] : -INFINITY;
-                    acc[i][j][e] = v;
-                    mx = fmaxf(mx, v);
-                    if (col == tgt) {
-                        zt = v;
-                        have = true;
-                    }
-                }
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float muse = mx == -INFINITY ? 0.f : mx;
-            const float nb = -muse * lf.k2;
-            float sum = 0.f;
-#pragma unroll
-            for (int j = 0; j < NI; ++j)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) sum += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[i][j][e], lf.k2, nb));
-            sum += __shfl_xor(sum, 32, 64);
-            if (r < M) {
-                if (half == 0) {
-                    float* p = lf.part + ((int64_t)r * lf.blocks + blk) * 2;
-                    p[0] = mx;
-                    p[1] = sum;
-                }
-                if (have) lf.target_logit[r] = zt;
-            }
-        }
-    } else if constexpr (EPI == kEpiLogitsMax) {
-        // transposed accumulators: a lane owns a row and, per register quad, four consecutive columns
-        const int half = lane >> 5;
-        const int blk = (n0 / BN) * WN + wn;
-        const int cbase = n0 + wn * TN;
-        float* C = (float*)Cv;
-#pragma unroll
-        for (int i = 0; i < MI; ++i) {
-            const int r = m0 + wm * TM + i * 32 + (lane & 31);
-            float mx = -INFINITY;
-#pragma unroll
-            for (int j = 0; j < NI; ++j)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int col = cbase + j * 32 + 8 * q + 4 * half;
-                    if (r < M && col < N) {  // N is a multiple of 4 (checked by the launcher): whole quads
-                        const float4 v = float4{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2],
-                                                acc[i][j][4 * q + 3]};
-                        *(float4*)(C + (int64_t)r * ldc + col) = v;
-                        mx = fmaxf(fmaxf(mx, fmaxf(v.x, v.y)), fmaxf(v.z, v.w));
-                    }
-                }
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            if (r < M && half == 0) lf.part[(int64_t)r * lf.blocks + blk] = mx;
-        }
-    } else if constexpr (EPI == kEpiRope) {
+    if constexpr (EPI == kEpiRope) {
         // The tile is BM rows of one head (BN = head_dim = 128, checked by the launcher).  The
         // accumulators go to LDS as fp32 [BM][BN + 1]; the rotation pairs (i, i + 64) of a row
         // then sit in one place whatever wave produced them.  q is rotated and stored to C, k is
@@ -812,6 +755,279 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const bf16* __res
         else
             gemm_epilogue<MI, NI, TM, TN, EPI>(acc, Cv, ldc, M, N, m0, n0, wm, wn, lane, tc.split);
     }
+}
+
+// ---------------------------------------------------------------------------
+// Two-stage direct-to-LDS kernel, second form: a workgroup walks over several tiles (virtual block
+// ids blockIdx.x, blockIdx.x + gridDim.x, ...), the loads of the next tile's first two slabs go out
+// during the last two slabs of the current one, and inside a slab every MFMA is followed by one
+// fragment read / one load so that the matrix pipe never waits behind a burst of memory instructions.
+// ---------------------------------------------------------------------------
+__device__ inline void dma_load16_s(const void* sbase, uint32_t voff, uint32_t lds_byte_addr) {
+    asm volatile(
+        "s_mov_b32 m0, %2\n\t"
+        "s_nop 0\n\t"
+        "global_load_lds_dwordx4 %0, %1\n\t"
+        :
+        : "v"(voff), "s"(sbase), "s"(lds_byte_addr)
+        : "memory");
+}
+
+template <int MI, int NI, int TM, int TN, int BN, int WN, int EPI, int SWIGLU>
+__device__ inline void dma2_epilogue(f32x16_t (&acc)[MI][NI], void* __restrict__ Cv, int64_t ldc, int M, int N, int m0,
+                                     int n0, int wm, int wn, int lane, int split, const LseFuse& lf) {
+    constexpr bool kTrans = EPI != kEpiStore;
+    if constexpr (EPI == kEpiLse) {
+        const int half = lane >> 5;
+        const int blk = (n0 / BN) * WN + wn;
+        const int cbase = n0 + wn * TN;
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+            const int r = m0 + wm * TM + i * 32 + (lane & 31);
+            const int tgt = r < M ? lf.target[r] : -1;
+            float mx = -INFINITY, zt = 0.f;
+            bool have = false;
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int col = cbase + j * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
+                    const float v = col < N ? acc[i][j][e] : -INFINITY;
+                    acc[i][j][e] = v;
+                    mx = fmaxf(mx, v);
+                    if (col == tgt) {
+                        zt = v;
+                        have = true;
+                    }
+                }
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float muse = mx == -INFINITY ? 0.f : mx;
+            const float nb = -muse * lf.k2;
+            float sum = 0.f;
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) sum += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[i][j][e], lf.k2, nb));
+            sum += __shfl_xor(sum, 32, 64);
+            if (r < M) {
+                if (half == 0) {
+                    float* p = lf.part + ((int64_t)r * lf.blocks + blk) * 2;
+                    p[0] = mx;
+                    p[1] = sum;
+                }
+                if (have) lf.target_logit[r] = zt;
+            }
+        }
+    } else if constexpr (EPI == kEpiLogitsMax) {
+        // transposed accumulators: a lane owns a row and, per register quad, four consecutive columns
+        const int half = lane >> 5;
+        const int blk = (n0 / BN) * WN + wn;
+        const int cbase = n0 + wn * TN;
+        float* C = (float*)Cv;
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+            const int r = m0 + wm * TM + i * 32 + (lane & 31);
+            float mx = -INFINITY;
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int col = cbase + j * 32 + 8 * q + 4 * half;
+                    if (r < M && col < N) {  // N is a multiple of 4 (checked by the launcher): whole quads
+                        const float4 v = float4{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2],
+                                                acc[i][j][4 * q + 3]};
+                        *(float4*)(C + (int64_t)r * ldc + col) = v;
+                        mx = fmaxf(fmaxf(mx, fmaxf(v.x, v.y)), fmaxf(v.z, v.w));
+                    }
+                }
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            if (r < M && half == 0) lf.part[(int64_t)r * lf.blocks + blk] = mx;
+        }
+    } else {
+        if constexpr (kTrans)
+            gemm_epilogue_t<MI, NI, TM, TN, EPI, SWIGLU>(acc, Cv, ldc, M, N, m0, n0, wm, wn, lane, split);
+        else
+            gemm_epilogue<MI, NI, TM, TN, EPI>(acc, Cv, ldc, M, N, m0, n0, wm, wn, lane, split);
+    }
+}
+
+template <int BM, int BN, int WM, int WN, int EPI, int SWIGLU>
+__global__ __launch_bounds__(WM* WN * 64) void gemm_dma2_kernel(const bf16* __restrict__ A, int64_t lda,
+                                                                const bf16* __restrict__ W, int64_t ldw,
+                                                                void* __restrict__ Cv, int64_t ldc, int M,
+                                                                int N, int K, int grid_m, int grid_n,
+                                                                int n_tiles, int splits, int k_per_split, int F,
+                                                                int n_vblocks, LseFuse lf) {
+    constexpr int BK = 64, KS = 4;
+    constexpr int NW = WM * WN;
+    constexpr int TM = BM / WM, TN = BN / WN;
+    constexpr int MI = TM / 32, NI = TN / 32;
+    constexpr int A_INST = BM / 8 / NW, B_INST = BN / 8 / NW;  // a wave instruction fills 8 rows (1 KiB)
+    constexpr int A_STAGE = BM * BK, B_STAGE = BN * BK;        // elements
+    constexpr int N_INST = A_INST + B_INST;
+    static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile/wave mismatch");
+    static_assert(EPI != kEpiRope, "no LDS-staged epilogue here");
+    constexpr bool kTrans = EPI != kEpiStore;
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    bf16* As = (bf16*)smem_raw;        // [2][BM][BK]
+    bf16* Bs = As + 2 * A_STAGE;       // [2][BN][BK]
+    const uint32_t lds_a = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem_raw;
+    const uint32_t lds_b = lds_a + 2 * A_STAGE * 2;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave % WM, wn = wave / WM;
+    int vb = blockIdx.x;
+    TileCoord tc = tile_coord(n_tiles, splits, grid_m, grid_n, vb);
+    if (!tc.ok) return;
+
+    // Load addressing: instruction j of this wave fills rows (j * NW + wave) * 8 + lane / 8 of a stage;
+    // the lane stores at position lane % 8 and therefore fetches piece (lane % 8) ^ swizzle(row).  The
+    // address is a per-tile uniform base (scalar registers) plus a 32-bit per-lane byte offset.
+    struct Src {
+        const bf16* a_base;
+        const bf16* b_base;
+        uint32_t a_off[A_INST], b_off[B_INST];
+        int nk;
+    };
+    auto setup = [&](const TileCoord& t, Src& o) {
+        const int m0 = t.bm * BM, n0 = t.bn * BN;
+        const int k_begin = t.split * k_per_split;
+        const int k_end = min(K, k_begin + k_per_split);
+        o.nk = (k_end - k_begin) / BK;
+        o.a_base = A + (int64_t)m0 * lda + k_begin;
+        o.b_base = W + k_begin;
+#pragma unroll
+        for (int j = 0; j < A_INST; ++j) {
+            const int row = (j * NW + wave) * 8 + (lane >> 3);
+            const int piece = (lane & 7) ^ lds_swizzle<BK>(row);
+            o.a_off[j] = (uint32_t)(((int64_t)min(row, M - 1 - m0) * lda + piece * 8) * 2);
+        }
+#pragma unroll
+        for (int j = 0; j < B_INST; ++j) {
+            const int row = (j * NW + wave) * 8 + (lane >> 3);
+            const int piece = (lane & 7) ^ lds_swizzle<BK>(row);
+            o.b_off[j] = (uint32_t)(((int64_t)weight_row<SWIGLU>(min(n0 + row, N - 1), F) * ldw + piece * 8) * 2);
+        }
+    };
+    // instruction t (A first, then B) of slab sl of tile source o into stage st
+    auto dma_one = [&](const Src& o, int sl, int st, int t) __attribute__((always_inline)) {
+        if (t < A_INST)
+            dma_load16_s(o.a_base + sl * BK, o.a_off[t], lds_a + (st * A_STAGE + (t * NW + wave) * 512) * 2);
+        else
+            dma_load16_s(o.b_base + sl * BK, o.b_off[t - A_INST], lds_b + (st * B_STAGE + ((t - A_INST) * NW + wave) * 512) * 2);
+    };
+
+    Src cur;
+    setup(tc, cur);
+    f32x16_t acc[MI][NI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+    const int frag_row = lane & 31;
+    const int frag_g = lds_swizzle<BK>(frag_row);
+    const int frag_half = lane >> 5;
+    const int a_frag = (wm * TM + frag_row) * BK, b_frag = (wn * TN + frag_row) * BK;
+    const int piece0 = (frag_half ^ frag_g) * 8;
+    bf16x8_t af[2][MI], bfr[2][NI];
+
+#pragma unroll
+    for (int t = 0; t < N_INST; ++t) dma_one(cur, 0, 0, t);
+#pragma unroll
+    for (int t = 0; t < N_INST; ++t) dma_one(cur, 1, 1, t);
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N_INST) : "memory");
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < NI; ++j) bfr[0][j] = *(const bf16x8_t*)(Bs + b_frag + j * 32 * BK + piece0);
+#pragma unroll
+    for (int i = 0; i < MI; ++i) af[0][i] = *(const bf16x8_t*)(As + a_frag + i * 32 * BK + piece0);
+
+    // One slab (g = running slab count of this workgroup: stage g & 1).  The loads that go out in its
+    // last k-step fetch slab dma_sl of the tile `cur` describes, into this slab's stage.
+    auto slab_body = [&](const int g, const int dma_sl) __attribute__((always_inline)) {
+        const int stage = g & 1;
+        const bf16* as = As + stage * A_STAGE + a_frag;
+        const bf16* bs = Bs + stage * B_STAGE + b_frag;
+#pragma unroll
+        for (int ks = 0; ks < KS - 1; ++ks) {
+            const int c = ks & 1, n = c ^ 1;
+            const int piece = (((ks + 1) * 2 + frag_half) ^ frag_g) * 8;
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NI; ++j) {
+                    const int t = i * NI + j;
+                    acc[i][j] = kTrans ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[c][j], af[c][i], acc[i][j], 0, 0, 0)
+                                       : __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[c][i], bfr[c][j], acc[i][j], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (t < NI) bfr[n][t] = *(const bf16x8_t*)(bs + t * 32 * BK + piece);
+                    else if (t < NI + MI) af[n][t - NI] = *(const bf16x8_t*)(as + (t - NI) * 32 * BK + piece);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+        }
+        // Last k-step: its fragments are in registers.  Once every wave's are, this stage is free, and the
+        // following slab has landed in the other stage.
+        constexpr int c = (KS - 1) & 1, n = c ^ 1;
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        __syncthreads();
+        const bf16* as1 = As + (stage ^ 1) * A_STAGE + a_frag;
+        const bf16* bs1 = Bs + (stage ^ 1) * B_STAGE + b_frag;
+        constexpr int kPer = (N_INST + MI * NI - 1) / (MI * NI);
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j) {
+                const int t = i * NI + j;
+                acc[i][j] = kTrans ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[c][j], af[c][i], acc[i][j], 0, 0, 0)
+                                   : __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[c][i], bfr[c][j], acc[i][j], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (t < NI) bfr[n][t] = *(const bf16x8_t*)(bs1 + t * 32 * BK + piece0);
+                else if (t < NI + MI) af[n][t - NI] = *(const bf16x8_t*)(as1 + (t - NI) * 32 * BK + piece0);
+#pragma unroll
+                for (int d = 0; d < kPer; ++d)
+                    if (t * kPer + d < N_INST) dma_one(cur, dma_sl, stage, t * kPer + d);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+    };
+
+    // this workgroup's tiles: virtual blocks blockIdx.x + i * gridDim.x while they map to a work item
+    int n_my = 0;
+    {
+        const int total = n_tiles * splits;
+        const int xcd = blockIdx.x % kXcd;
+        const int cnt = (int)(((int64_t)(xcd + 1) * total) / kXcd) - (int)(((int64_t)xcd * total) / kXcd);
+        const int slot = blockIdx.x / kXcd, wpx = gridDim.x / kXcd;
+        if (slot < cnt) n_my = (cnt - slot + wpx - 1) / wpx;
+    }
+    int g = 0;
+#pragma clang loop unroll(disable)
+    for (int it = 0; it < n_my; ++it) {
+        // the tile after this one; after the last tile the loads wrap to the same tile (fetched, never used)
+        TileCoord ntc = tc;
+        if (it + 1 < n_my) ntc = tile_coord(n_tiles, splits, grid_m, grid_n, vb + (int)gridDim.x);
+        const int nk = cur.nk;  // >= 2 (checked by the launcher)
+#pragma clang loop unroll(disable)
+        for (int kt = 0; kt < nk; ++kt) {
+            if (kt == nk - 2) setup(ntc, cur);  // this tile's loads are all out: the addresses become the next tile's
+            slab_body(g, kt + 2 < nk ? kt + 2 : kt + 2 - nk);
+            ++g;
+        }
+        dma2_epilogue<MI, NI, TM, TN, BN, WN, EPI, SWIGLU>(acc, Cv, ldc, M, N, tc.bm * BM, tc.bn * BN, wm, wn, lane, tc.split, lf);
+        tc = ntc;
+        vb += (int)gridDim.x;
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
 // Sum the K-split partials [splits][M][N] and apply the epilogue.  One thread per output
@@ -1081,6 +1297,14 @@ bool norm_fusable(const GemmArgs& a) {
            ((uintptr_t)a.norm_out % 8 == 0) && ((uintptr_t)a.norm_gain % 8 == 0);
 }
 
+// What gemm_dma2_kernel needs beyond whole 64-deep slabs: at least two slabs in every K split, and
+// weight rows within reach of a 32-bit byte offset.
+bool dma2_ok(const GemmArgs& a, int splits) {
+    const int k_per_split = ceil_div(ceil_div(a.K, splits), kBK) * kBK;
+    return a.K % kBK == 0 && a.path != 2 && k_per_split >= 2 * kBK && a.K - (splits - 1) * k_per_split >= 2 * kBK &&
+           (uint64_t)a.N * (uint64_t)a.ldw * sizeof(bf16) < (1ull << 32);
+}
+
 template <int BM, int BN, int WM, int WN, int EPI, int SWIGLU, int DST = kDmaStages, int DBK = kDmaBK>
 hipError_t launch_one(const GemmArgs& a, int splits, void* out, hipStream_t s) {
     // direct-to-LDS pipeline shape: DBK-deep slabs in DST stages
@@ -1091,7 +1315,31 @@ hipError_t launch_one(const GemmArgs& a, int splits, void* out, hipStream_t s) {
     const dim3 grid((unsigned)(per_xcd * kXcd)), block(WM * WN * 64);
     // direct-to-LDS loads need whole 64-deep slabs; path 2 keeps the register-staged kernel
     const bool dma = a.K % kBK == 0 && a.path != 2;
-    if (dma) {
+    // The wide two-stage tiles run on gemm_dma2_kernel (what it does not take goes to the register-staged kernel).
+    constexpr bool kWide = DST == 2 && DBK == 64 && BM >= 128 && EPI != kEpiRope;
+    if constexpr (kWide) {
+        if (dma2_ok(a, splits)) {
+            const size_t lds = (size_t)2 * (BM + BN) * 64 * sizeof(bf16);
+            auto kern = gemm_dma2_kernel<BM, BN, WM, WN, EPI, SWIGLU>;
+            static bool attr_set2 = false;  // one flag per template instance
+            if (!attr_set2) {
+                hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                if (e != hipSuccess) return e;
+                attr_set2 = true;
+            }
+            // Many rounds of tiles: one resident workgroup per CU slot walks its share of them (no gap
+            // between tiles, the next tile's first loads overlap the epilogue).  Few rounds: one tile per
+            // workgroup, placed by the dispatcher.
+            const int nvb = per_xcd * kXcd;
+            const int resident = 256 * (lds > 80 * 1024 ? 1 : 2);
+            const int g = nvb >= 4 * resident ? resident : nvb;
+            kern<<<dim3((unsigned)g), block, lds, s>>>((const bf16*)a.A, a.lda, (const bf16*)a.W, a.ldw, out, a.ldc, a.M, a.N,
+                                                       a.K, gm, gn, n_tiles, splits, k_per_split, a.N / 2, nvb,
+                                                       (EPI == kEpiLse && a.lse) ? *a.lse
+                                                       : (EPI == kEpiLogitsMax && a.block_max) ? *a.block_max : LseFuse{});
+            return hipGetLastError();
+        }
+    } else if (dma) {
         size_t lds = (size_t)DST * (BM + BN) * DBK * sizeof(bf16);
         if (EPI == kEpiRope) {  // fp32 tile [BM][BN + 1] + per-row position and page
             const size_t need = (size_t)BM * (BN + 1) * 4 + (size_t)(BM + (BM & 1)) * 4 + (size_t)BM * 8;
@@ -1106,9 +1354,7 @@ hipError_t launch_one(const GemmArgs& a, int splits, void* out, hipStream_t s) {
         }
         kern<<<grid, block, lds, s>>>((const bf16*)a.A, a.lda, (const bf16*)a.W, a.ldw, out, a.ldc, a.M, a.N, a.K,
                                       gm, gn, n_tiles, splits, k_per_split, a.N / 2,
-                                      (EPI == kEpiRope && a.rope) ? *a.rope : RopeKvArgs{},
-                                      (EPI == kEpiLse && a.lse) ? *a.lse
-                                      : (EPI == kEpiLogitsMax && a.block_max) ? *a.block_max : LseFuse{});
+                                      (EPI == kEpiRope && a.rope) ? *a.rope : RopeKvArgs{}, LseFuse{});
         return hipGetLastError();
     }
     if constexpr (EPI == kEpiRope || EPI == kEpiLse || EPI == kEpiLogitsMax) {
@@ -1217,7 +1463,7 @@ hipError_t launch_generic(const GemmArgs& a, hipStream_t s) {
 }  // namespace
 
 int gemm_fuses_lse(const GemmArgs& a) {
-    if (a.epilogue != kEpiStoreF32 || !mfma_ok(a) || a.K % kBK != 0 || a.path == 2) return 0;
+    if (a.epilogue != kEpiStoreF32 || !mfma_ok(a) || !dma2_ok(a, 1)) return 0;
     if (pick_tile(a).id != kKidGemm256) return 0;
     return ceil_div(a.N, 256) * 4;  // one block per wave column of a 256-wide tile
 }
