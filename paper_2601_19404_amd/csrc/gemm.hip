@@ -338,11 +338,11 @@ __device__ inline int weight_row(int n, int F) {
 // and 4 weight slabs through its L2.
 struct TileCoord {
     int bm, bn, split;
-    bool ok;
+    int ok;  // an int, not a bool: copies of the struct then stay in registers
 };
 // vb: the virtual block id to map (a workgroup that walks several tiles), or < 0: blockIdx.x.
 __device__ inline TileCoord tile_coord(int n_tiles, int splits, int grid_m, int grid_n, int vb = -1) {
-    TileCoord t{0, 0, 0, false};
+    TileCoord t{0, 0, 0, 0};
     const int total = n_tiles * splits;
     const int bid = vb < 0 ? (int)blockIdx.x : vb;
     const int xcd = bid % kXcd;
@@ -369,7 +369,7 @@ __device__ inline TileCoord tile_coord(int n_tiles, int splits, int grid_m, int 
     r -= blk * 8 * width;
     t.bm = blk * 8 + r % height;
     t.bn = band * 4 + r / height;
-    t.ok = true;
+    t.ok = 1;
     return t;
 }
 
@@ -758,10 +758,11 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma_kernel(const bf16* __res
 }
 
 // ---------------------------------------------------------------------------
-// Two-stage direct-to-LDS kernel, second form: a workgroup walks over several tiles (virtual block
-// ids blockIdx.x, blockIdx.x + gridDim.x, ...), the loads of the next tile's first two slabs go out
-// during the last two slabs of the current one, and inside a slab every MFMA is followed by one
-// fragment read / one load so that the matrix pipe never waits behind a burst of memory instructions.
+// Direct-to-LDS kernel of the wide tiles, S stages (2, or 3 where the tile leaves room in the 160 KiB
+// of LDS).  A workgroup walks over several tiles (virtual block ids blockIdx.x, blockIdx.x + gridDim.x,
+// ...): the loads of the next tile's first S slabs go out during the last S slabs of the current one
+// (none after the workgroup's last tile), and inside a slab every MFMA is followed by one fragment read
+// / one load so that the matrix pipe never waits behind a burst of memory instructions.
 // ---------------------------------------------------------------------------
 __device__ inline void dma_load16_s(const void* sbase, uint32_t voff, uint32_t lds_byte_addr) {
     asm volatile(
@@ -851,7 +852,7 @@ __device__ inline void dma2_epilogue(f32x16_t (&acc)[MI][NI], void* __restrict__
     }
 }
 
-template <int BM, int BN, int WM, int WN, int EPI, int SWIGLU>
+template <int BM, int BN, int WM, int WN, int EPI, int SWIGLU, int S = 2>
 __global__ __launch_bounds__(WM* WN * 64) void gemm_dma2_kernel(const bf16* __restrict__ A, int64_t lda,
                                                                 const bf16* __restrict__ W, int64_t ldw,
                                                                 void* __restrict__ Cv, int64_t ldc, int M,
@@ -870,10 +871,10 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma2_kernel(const bf16* __re
     constexpr bool kTrans = EPI != kEpiStore;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    bf16* As = (bf16*)smem_raw;        // [2][BM][BK]
-    bf16* Bs = As + 2 * A_STAGE;       // [2][BN][BK]
+    bf16* As = (bf16*)smem_raw;        // [S][BM][BK]
+    bf16* Bs = As + S * A_STAGE;       // [S][BN][BK]
     const uint32_t lds_a = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem_raw;
-    const uint32_t lds_b = lds_a + 2 * A_STAGE * 2;
+    const uint32_t lds_b = lds_a + S * A_STAGE * 2;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -912,7 +913,8 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma2_kernel(const bf16* __re
         }
     };
     // instruction t (A first, then B) of slab sl of tile source o into stage st
-    auto dma_one = [&](const Src& o, int sl, int st, int t) __attribute__((always_inline)) {
+    auto dma_one = [&](const Src& o, int sl, int st, int t, int on) __attribute__((always_inline)) {
+        if (!on) return;  // uniform
         if (t < A_INST)
             dma_load16_s(o.a_base + sl * BK, o.a_off[t], lds_a + (st * A_STAGE + (t * NW + wave) * 512) * 2);
         else
@@ -937,10 +939,10 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma2_kernel(const bf16* __re
     bf16x8_t af[2][MI], bfr[2][NI];
 
 #pragma unroll
-    for (int t = 0; t < N_INST; ++t) dma_one(cur, 0, 0, t);
+    for (int sl = 0; sl < S; ++sl)
 #pragma unroll
-    for (int t = 0; t < N_INST; ++t) dma_one(cur, 1, 1, t);
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N_INST) : "memory");
+        for (int t = 0; t < N_INST; ++t) dma_one(cur, sl, sl, t, 1);
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 1) * N_INST) : "memory");
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < NI; ++j) bfr[0][j] = *(const bf16x8_t*)(Bs + b_frag + j * 32 * BK + piece0);
@@ -949,8 +951,8 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma2_kernel(const bf16* __re
 
     // One slab (g = running slab count of this workgroup: stage g & 1).  The loads that go out in its
     // last k-step fetch slab dma_sl of the tile `cur` describes, into this slab's stage.
-    auto slab_body = [&](const int g, const int dma_sl) __attribute__((always_inline)) {
-        const int stage = g & 1;
+    auto slab_body = [&](const int stage, const int dma_sl, const int on) __attribute__((always_inline)) {
+        const int stage1 = stage + 1 == S ? 0 : stage + 1;
         const bf16* as = As + stage * A_STAGE + a_frag;
         const bf16* bs = Bs + stage * B_STAGE + b_frag;
 #pragma unroll
@@ -973,10 +975,15 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma2_kernel(const bf16* __re
         // Last k-step: its fragments are in registers.  Once every wave's are, this stage is free, and the
         // following slab has landed in the other stage.
         constexpr int c = (KS - 1) & 1, n = c ^ 1;
-        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        // the S - 2 slabs after the next one may still be in flight -- unless the loads have stopped (tail of the
+        // workgroup's last tile): then everything outstanding is waited for
+        if (S > 2 && on)
+            asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((S - 2) * N_INST) : "memory");
+        else
+            asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
         __syncthreads();
-        const bf16* as1 = As + (stage ^ 1) * A_STAGE + a_frag;
-        const bf16* bs1 = Bs + (stage ^ 1) * B_STAGE + b_frag;
+        const bf16* as1 = As + stage1 * A_STAGE + a_frag;
+        const bf16* bs1 = Bs + stage1 * B_STAGE + b_frag;
         constexpr int kPer = (N_INST + MI * NI - 1) / (MI * NI);
 #pragma unroll
         for (int i = 0; i < MI; ++i)
@@ -990,7 +997,7 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma2_kernel(const bf16* __re
                 else if (t < NI + MI) af[n][t - NI] = *(const bf16x8_t*)(as1 + (t - NI) * 32 * BK + piece0);
 #pragma unroll
                 for (int d = 0; d < kPer; ++d)
-                    if (t * kPer + d < N_INST) dma_one(cur, dma_sl, stage, t * kPer + d);
+                    if (t * kPer + d < N_INST) dma_one(cur, dma_sl, stage, t * kPer + d, on);
                 __builtin_amdgcn_sched_barrier(0);
             }
     };
@@ -1004,18 +1011,19 @@ __global__ __launch_bounds__(WM* WN * 64) void gemm_dma2_kernel(const bf16* __re
         const int slot = blockIdx.x / kXcd, wpx = gridDim.x / kXcd;
         if (slot < cnt) n_my = (cnt - slot + wpx - 1) / wpx;
     }
-    int g = 0;
+    int stage = 0;
 #pragma clang loop unroll(disable)
     for (int it = 0; it < n_my; ++it) {
-        // the tile after this one; after the last tile the loads wrap to the same tile (fetched, never used)
+        // the tile after this one (after the last one no loads go out)
+        const bool last = it + 1 == n_my;
         TileCoord ntc = tc;
-        if (it + 1 < n_my) ntc = tile_coord(n_tiles, splits, grid_m, grid_n, vb + (int)gridDim.x);
-        const int nk = cur.nk;  // >= 2 (checked by the launcher)
+        if (!last) ntc = tile_coord(n_tiles, splits, grid_m, grid_n, vb + (int)gridDim.x);
+        const int nk = cur.nk;  // >= S (checked by the launcher)
 #pragma clang loop unroll(disable)
         for (int kt = 0; kt < nk; ++kt) {
-            if (kt == nk - 2) setup(ntc, cur);  // this tile's loads are all out: the addresses become the next tile's
-            slab_body(g, kt + 2 < nk ? kt + 2 : kt + 2 - nk);
-            ++g;
+            if (kt == nk - S && !last) setup(ntc, cur);  // this tile's loads are all out: the addresses become the next tile's
+            slab_body(stage, kt + S < nk ? kt + S : kt + S - nk, (kt + S < nk || !last) ? 1 : 0);
+            stage = stage + 1 == S ? 0 : stage + 1;
         }
         dma2_epilogue<MI, NI, TM, TN, BN, WN, EPI, SWIGLU>(acc, Cv, ldc, M, N, tc.bm * BM, tc.bn * BN, wm, wn, lane, tc.split, lf);
         tc = ntc;
@@ -1233,11 +1241,10 @@ TileCfg pick_tile(const GemmArgs& a) {
     // tiles still fit one round and each is a quarter cheaper.
     if (a.epilogue == kEpiSwiglu && a.M > 128 && t256 >= 128 && t256 <= 256 && a.K % kBK == 0 && a.path != 2 &&
         (a.N / 2) % 16 == 0 && ceil_div(a.M, 256) * ceil_div(a.N, 192) <= 256) {
-        // 256x160 tiles (four waves of 64x160) still fit one round and put work on more CUs.  Measured:
-        // they win once K is deep enough for the main loop to outweigh the longer per-wave prologue and
-        // epilogue (K = 3584, N = 37888: 90 -> 81 us at 256 rows, 192 -> 149 us at 512 rows; K = 1536:
-        // 39.5 -> 40.2 us at 512 rows).
-        if (a.K >= 2048 && ceil_div(a.M, 256) * ceil_div(a.N, 160) <= 256) return TileCfg{kKidGemm256x160, 256, 160};
+        // 256x160 tiles (four waves of 64x160, three stages) still fit one round and put work on more CUs.
+        // Measured with weights streamed from HBM: K = 1536, N = 17920, 512 rows: 39.2 -> 34.3 us;
+        // K = 3584, N = 37888, 256 rows: 87.5 -> 78.8 us.
+        if (a.K >= 3 * kBK && ceil_div(a.M, 256) * ceil_div(a.N, 160) <= 256) return TileCfg{kKidGemm256x160, 256, 160};
         return TileCfg{kKidGemm256x192, 256, 192};
     }
     // up to 128 rows a 256-row tile multiplies mostly padding
@@ -1297,11 +1304,12 @@ bool norm_fusable(const GemmArgs& a) {
            ((uintptr_t)a.norm_out % 8 == 0) && ((uintptr_t)a.norm_gain % 8 == 0);
 }
 
-// What gemm_dma2_kernel needs beyond whole 64-deep slabs: at least two slabs in every K split, and
+// What gemm_dma2_kernel needs beyond whole 64-deep slabs: at least as many slabs as stages in every K split, and
 // weight rows within reach of a 32-bit byte offset.
-bool dma2_ok(const GemmArgs& a, int splits) {
+bool dma2_ok(const GemmArgs& a, int splits, int stages = 2) {
     const int k_per_split = ceil_div(ceil_div(a.K, splits), kBK) * kBK;
-    return a.K % kBK == 0 && a.path != 2 && k_per_split >= 2 * kBK && a.K - (splits - 1) * k_per_split >= 2 * kBK &&
+    return a.K % kBK == 0 && a.path != 2 && k_per_split >= stages * kBK &&
+           a.K - (splits - 1) * k_per_split >= stages * kBK &&
            (uint64_t)a.N * (uint64_t)a.ldw * sizeof(bf16) < (1ull << 32);
 }
 
@@ -1318,9 +1326,13 @@ hipError_t launch_one(const GemmArgs& a, int splits, void* out, hipStream_t s) {
     // The wide two-stage tiles run on gemm_dma2_kernel (what it does not take goes to the register-staged kernel).
     constexpr bool kWide = DST == 2 && DBK == 64 && BM >= 128 && EPI != kEpiRope;
     if constexpr (kWide) {
-        if (dma2_ok(a, splits)) {
-            const size_t lds = (size_t)2 * (BM + BN) * 64 * sizeof(bf16);
-            auto kern = gemm_dma2_kernel<BM, BN, WM, WN, EPI, SWIGLU>;
+        // The decode gate/up tile leaves room for a third stage in the 160 KiB of LDS: two slabs in flight
+        // feed a workgroup that streams its weights from HBM (measured at 512 rows, weights not cached:
+        // 35.8 -> 34.3 us at K = 1536, 81.1 -> 78.8 us at K = 3584).
+        constexpr int S = (BM == 256 && BN == 160) ? 3 : 2;
+        if (dma2_ok(a, splits, S)) {
+            const size_t lds = (size_t)S * (BM + BN) * 64 * sizeof(bf16);
+            auto kern = gemm_dma2_kernel<BM, BN, WM, WN, EPI, SWIGLU, S>;
             static bool attr_set2 = false;  // one flag per template instance
             if (!attr_set2) {
                 hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
