@@ -97,6 +97,34 @@ def test_gemm_swiglu(rpo, M, F, K, path, ws_mb):
     assert np.all(err <= tol), f"max err {err.max()}"
 
 
+@pytest.mark.parametrize("shape", [(8200, 8256, 128), (8200, 8256, 192), (16500, 4000, 256), (8192, 6144, 192)])
+def test_gemm_resident_workgroups_walk_many_tiles(rpo, shape):
+    """1000+ tiles: the launch keeps one resident workgroup per CU that walks its share of the tiles
+    (256x256 and, for the narrow N, 256x192 tiles; ragged last row and column tiles), with the minimum
+    of two K slabs and with an odd slab count (the LDS stage a tile starts in alternates)."""
+    for epi in (0, 1, 2):
+        _gemm_case(rpo, *shape, torch.bfloat16, epi, path=0, seed=11)
+
+
+@pytest.mark.parametrize("M,F,K", [(8200, 4128, 192), (8192, 4096, 128), (512, 8960, 192), (512, 8960, 256), (384, 8960, 1536)])
+def test_gemm_swiglu_resident_and_three_stage_tiles(rpo, M, F, K):
+    """Fused gate/up on the resident-workgroup launch (many tiles) and on the three-stage 256x160 decode
+    tile with as few K slabs as it has stages."""
+    g = torch.Generator().manual_seed(M + F + K)
+    a = torch.randn(M, K, generator=g).to(torch.bfloat16)
+    w = (torch.randn(2 * F, K, generator=g) * 0.05).to(torch.bfloat16)
+    gu = T.lm_head({"lm_head": w.float().numpy()}, a.float().numpy())
+    ref = T.silu(gu[:, :F]) * gu[:, F:]
+    c = torch.zeros(M, F, dtype=torch.bfloat16, device="cuda")
+    rpo.rpo_set_kernel_path(0)
+    rpo.rpo_gemm_nt(a.cuda(), w.cuda(), c, 3, None)
+    torch.cuda.synchronize()
+    got = c.float().cpu().numpy().astype(np.float64)
+    err = np.abs(got - ref)
+    tol = 2.0 ** -8 * np.abs(ref) + 3e-5 * np.sqrt(K)
+    assert np.all(err <= tol), f"max err {err.max()}"
+
+
 def test_gemm_mfma_bf16_padded_strides(rpo):
     _gemm_case(rpo, 70, 90, 128, torch.bfloat16, 1, path=0, pad=8)
     _gemm_case(rpo, 70, 90, 128, torch.bfloat16, 2, path=0, pad=8)
