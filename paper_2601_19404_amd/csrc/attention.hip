@@ -103,15 +103,18 @@ static hipError_t launch_attn_generic(const AttnArgs& a, hipStream_t s) {
 // ---------------------------------------------------------------------------
 // MFMA core
 // ---------------------------------------------------------------------------
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
 constexpr int kDh = 128;      // head_dim of the MFMA kernels
 constexpr int kPt = 64;       // tokens per page
 // LDS tiles are unpadded; bank conflicts of the fragment reads are avoided by permuting the 16-byte
 // pieces of a row with the row index.  K tile [64 tokens][128 channels]: piece p of row r sits at
 // p ^ (r & 15), so the 16-byte reads of sixteen consecutive rows (same piece) are spread evenly
 // over the banks whichever lanes the LDS serves together.
-// V^T tile [128 channels][64 tokens]: piece p (eight tokens) of row r sits at p ^ (r & 7) with its
-// two 8-byte halves exchanged when r & 8, so the 8-byte reads of sixteen consecutive rows (same
-// tokens) cover all 32 banks too.
+// V^T tile [128 channels][64 tokens]: inside a row the tokens are reordered so that the eight tokens a
+// lane group multiplies in one k-step of the second product (32 kk + 4 g + i and 32 kk + 16 + 4 g + i,
+// i < 4: the token order its probabilities leave the first product in) are one 16-byte piece, piece
+// 4 kk + g; piece p of row r sits at p ^ (r & 7) ^ ((r >> 3) & 1), which spreads the 16-byte reads of
+// sixteen consecutive rows (same piece) over the banks.
 constexpr int kKRow = kDh;  // LDS row of the K tile  [64][128]
 constexpr int kVRow = kPt;  // LDS row of the V^T tile [128][64]
 constexpr int kKTile = kPt * kKRow;
@@ -170,6 +173,7 @@ __device__ inline void attn_stream_pages(const bf16* const (&qptr)[NC], const in
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) lim_min = min(lim_min, __shfl_xor(lim_min, o, 64));
 
+    const f32x4_t zero4 = f32x4_t{0.f, 0.f, 0.f, 0.f};
     u32x4_t rk[4], rv[4];
     auto load_page = [&](int p) {
         const int64_t page = table[p];
@@ -187,10 +191,15 @@ __device__ inline void attn_stream_pages(const bf16* const (&qptr)[NC], const in
             const int c = tid + i * 256;
             const int kr = c >> 4;
             *(u32x4_t*)(Ks + buf * kKTile + kr * kKRow + (((c & 15) ^ (kr & 15)) << 3)) = rk[i];
-            // V block piece c = (token group c / 128, channel c % 128) -> LDS row = channel
-            const int vr = c & (kDh - 1);
-            const u32x4_t v = (vr & 8) ? u32x4_t{rv[i].z, rv[i].w, rv[i].x, rv[i].y} : rv[i];
-            *(u32x4_t*)(Vs + buf * kVTile + vr * kVRow + ((((c >> 7)) ^ (vr & 7)) << 3)) = v;
+            // V block piece c = (token group m = c / 128: tokens 8 m .. 8 m + 7, channel c % 128) -> LDS row =
+            // channel; tokens 8 m .. + 3 are half (m / 2) % 2 of piece 4 (m / 4) + (2 m) % 4, tokens 8 m + 4 .. + 7
+            // the same half of the piece after it
+            const int vr = c & (kDh - 1), m = c >> 7;
+            const int sw = (vr & 7) ^ ((vr >> 3) & 1);
+            const int pl = 4 * (m >> 2) + ((2 * m) & 3);
+            bf16* vrow = Vs + buf * kVTile + vr * kVRow + 4 * ((m >> 1) & 1);
+            *(u32x2_t*)(vrow + ((pl ^ sw) << 3)) = u32x2_t{rv[i].x, rv[i].y};
+            *(u32x2_t*)(vrow + (((pl + 1) ^ sw) << 3)) = u32x2_t{rv[i].z, rv[i].w};
         }
     };
 
@@ -208,13 +217,11 @@ __device__ inline void attn_stream_pages(const bf16* const (&qptr)[NC], const in
 #pragma unroll
             for (int mb = 0; mb < 4; ++mb) {
 #pragma unroll
-                for (int c = 0; c < NC; ++c) sc[c][mb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
                 for (int kk = 0; kk < 4; ++kk) {
                     const bf16x8_t ak = *(const bf16x8_t*)(ks + (mb * 16 + c16) * kKRow + (((kk * 4 + g) ^ c16) << 3));
 #pragma unroll
-                    for (int c = 0; c < NC; ++c)
-                        sc[c][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ak, bq[c][kk], sc[c][mb], 0, 0, 0);
+                    for (int c = 0; c < NC; ++c)  // the first product starts from one shared zero block
+                        sc[c][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ak, bq[c][kk], kk == 0 ? zero4 : sc[c][mb], 0, 0, 0);
                 }
             }
             bf16x8_t bp[NC][2];
@@ -274,12 +281,8 @@ __device__ inline void attn_stream_pages(const bf16* const (&qptr)[NC], const in
             for (int kk2 = 0; kk2 < 2; ++kk2) {
 #pragma unroll
                 for (int mb2 = 0; mb2 < 8; ++mb2) {
-                    // tokens 32 kk2 + 4 g .. + 3 = half (g & 1) of piece 4 kk2 + g / 2; "hi" is two pieces on
-                    const bf16* vrow = vs + (mb2 * 16 + c16) * kVRow + (((g & 1) ^ (c16 >> 3)) << 2);
-                    const int vp0 = 4 * kk2 + (g >> 1);
-                    const bf16x4_t lo = *(const bf16x4_t*)(vrow + ((vp0 ^ (c16 & 7)) << 3));
-                    const bf16x4_t hi = *(const bf16x4_t*)(vrow + (((vp0 + 2) ^ (c16 & 7)) << 3));
-                    const bf16x8_t av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    const bf16x8_t av = *(const bf16x8_t*)(vs + (mb2 * 16 + c16) * kVRow +
+                                                           (((4 * kk2 + g) ^ (c16 & 7) ^ (c16 >> 3)) << 3));
 #pragma unroll
                     for (int c = 0; c < NC; ++c)
                         st.ot[c][mb2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bp[c][kk2], st.ot[c][mb2], 0, 0, 0);
