@@ -121,6 +121,18 @@ constexpr int kKTile = kPt * kKRow;
 constexpr int kVTile = kDh * kVRow;
 constexpr size_t kAttnLds = (size_t)2 * (kKTile + kVTile) * sizeof(bf16);
 
+// Maximum over the four lanes l % 16, l % 16 + 16, + 32, + 48 (the lanes that share a query column), in
+// every one of them.  The two lane-swap instructions of gfx950 exchange rows of 16 (halves of 32) lanes
+// between two registers: fed the same value twice, they leave in every lane its own value and that of
+// lane ^ 16 (lane ^ 32) -- a register exchange, no trip through LDS as a general shuffle takes.
+__device__ inline float max_over_lane_groups(float v) {
+    typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+    u32x2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
 // NC = 16-column query tiles per wave: a wave multiplies every K / V fragment it reads from LDS
 // with NC query tiles, so the LDS traffic per flop falls with NC.
 template <int NC>
@@ -246,8 +258,7 @@ __device__ inline void attn_stream_pages(const bf16* const (&qptr)[NC], const in
 #pragma unroll
                         for (int i = 0; i < 4; ++i) mloc = fmaxf(mloc, sc[c][mb][i]);
                 }
-                mloc = fmaxf(mloc, __shfl_xor(mloc, 16, 64));
-                mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+                mloc = max_over_lane_groups(mloc);
                 const float mnew = fmaxf(st.m[c], mloc);
                 const float muse = (mnew == -INFINITY) ? 0.f : mnew;
                 const float alpha = __builtin_amdgcn_exp2f((st.m[c] - muse) * scale_log2);
