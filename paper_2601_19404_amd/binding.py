@@ -423,7 +423,7 @@ def rpo_probe_peaks(n_bytes: int = 1 << 30, stream=None):
 
 KERNEL_IDS = {"gemm256": 1, "gemm128": 3, "gemm64": 4, "gemm32": 5, "gemm64x64": 6,
               "gemm_generic": 7, "gemm256x192": 11, "attn_decode": 8, "attn_chunk": 9, "sample": 10,
-              "gemm256_swiglu": 12}
+              "gemm256_swiglu": 12, "gemm256x160": 13}
 
 
 def rpo_profile_start(kernel_id: int, every: int = 1) -> None:
