@@ -1339,12 +1339,13 @@ bool norm_fusable(const GemmArgs& a) {
 }
 
 // What gemm_dma2_kernel needs beyond whole 64-deep slabs: at least as many slabs as stages in every K split, and
-// weight rows within reach of a 32-bit byte offset.
+// the weight rows (from the matrix start) and a tile's activation rows within reach of a 32-bit byte offset.
 bool dma2_ok(const GemmArgs& a, int splits, int stages = 2) {
     const int k_per_split = ceil_div(ceil_div(a.K, splits), kBK) * kBK;
     return a.K % kBK == 0 && a.path != 2 && k_per_split >= stages * kBK &&
            a.K - (splits - 1) * k_per_split >= stages * kBK &&
-           (uint64_t)a.N * (uint64_t)a.ldw * sizeof(bf16) < (1ull << 32);
+           (uint64_t)a.N * (uint64_t)a.ldw * sizeof(bf16) < (1ull << 32) &&
+           (uint64_t)256 * (uint64_t)a.lda * sizeof(bf16) < (1ull << 32);  // a tile's activation rows as well
 }
 
 template <int BM, int BN, int WM, int WN, int EPI, int SWIGLU, int DST = kDmaStages, int DBK = kDmaBK>
